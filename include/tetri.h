@@ -1,0 +1,193 @@
+/*
+ * tetri.h -- C ABI of the MI355X (gfx950) chunked-prefill attention library.
+ *
+ * The library implements the data-parallel hot path of the prefill instance of TetriInfer
+ * (arxiv 2401.11181):
+ *   - Sec. 3.3.3 "Chunked Prefill": the scheduled prompts are sliced and merged, in order,
+ *     into fixed-size chunks of ChunkSize tokens, the last chunk of a batch is padded, the
+ *     model runs prefill one chunk at a time and a per-request variable records how far each
+ *     request has been prefilled;
+ *   - Sec. 2.1: prefill of a causal LLM produces the KV cache, so each chunk attends to all
+ *     earlier tokens of its own request(s) and to itself;
+ *   - Sec. 3.4 / Sec. 5: the KV cache is managed in pages.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C, no exceptions, no aborts: every call returns a tetri_status (or a count that
+ *     is negative on error); a message is kept in the handle (tetri_last_error).
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory owned by the caller.  The library never frees or reallocates
+ *     caller memory and allocates nothing per call.
+ *   - Launching entry points are asynchronous on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and never synchronise it.
+ *   - Host-checkable violations (null pointer, counts out of range, unsupported shape,
+ *     pointers not 16-byte aligned) are rejected with no kernel launched.  The contents of
+ *     device-resident metadata cannot be checked without a synchronisation; use
+ *     tetri_validate_chunk for that in tests.
+ *
+ * Tensor layouts (contiguous, row-major, bf16 unless stated)
+ *   q, out         [chunk_size][num_q_heads][head_dim]
+ *   k_new, v_new   [chunk_size][num_kv_heads][head_dim]
+ *   kv_pages       [num_pages][2 (0 = K, 1 = V)][num_kv_heads][page_size][head_dim]
+ *   block_table    [num_segs][max_blocks_per_seq] int32: physical page of logical page b of the
+ *                  request of segment s; must cover ceil((ctx_lens[s] + n_s) / page_size) pages
+ *   cu_chunk_q_lens[num_segs + 1] int32: prefix sums of the segment lengths n_s inside the
+ *                  chunk, cu[0] = 0, cu[num_segs] <= chunk_size; rows [cu[num_segs], chunk_size)
+ *                  are padding and belong to no request
+ *   ctx_lens       [num_segs] int32: tokens of the segment's request already in the cache
+ *                  before this chunk (the per-request progress variable of Sec. 3.3.3)
+ */
+#ifndef TETRI_H
+#define TETRI_H
+
+#include <stdint.h>
+
+#if defined(TETRI_BUILDING)
+#define TETRI_API __attribute__((visibility("default")))
+#else
+#define TETRI_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tetri_ctx tetri_ctx;
+
+typedef enum {
+    TETRI_OK = 0,
+    TETRI_ERR_INVALID_ARG = -1,   /* null/misaligned pointer, count out of range, bad metadata */
+    TETRI_ERR_UNSUPPORTED = -2,   /* shape or dtype this build has no kernel for */
+    TETRI_ERR_HIP = -3,           /* the HIP runtime reported an error (launch, copy, no device) */
+    TETRI_ERR_NOMEM = -4          /* host allocation failed or a caller-sized array is too small */
+} tetri_status;
+
+enum { TETRI_BF16 = 1 };
+
+typedef struct {
+    int32_t num_q_heads;          /* Hq                                                     */
+    int32_t num_kv_heads;         /* Hkv, Hq % Hkv == 0 (Hq / Hkv query heads share a KV head) */
+    int32_t head_dim;             /* 64 or 128                                              */
+    int32_t page_size;            /* 16                                                     */
+    int32_t chunk_size;           /* ChunkSize: rows of q / k_new / v_new / out             */
+    int32_t num_pages;            /* pages in kv_pages                                      */
+    int32_t max_blocks_per_seq;   /* row length of block_table                              */
+    int32_t max_segs_per_chunk;   /* upper bound of num_segs                                */
+    int32_t dtype;                /* TETRI_BF16                                             */
+} tetri_config;
+
+/* One slice of a request inside a chunk (Sec. 3.3.3: slicing and merging). */
+typedef struct {
+    int32_t req;                  /* index into prompt_lens                                 */
+    int32_t start;                /* tokens of this request prefilled before this chunk     */
+    int32_t len;                  /* tokens of this request in this chunk (> 0)             */
+} tetri_segment;
+
+/*
+ * Create / destroy a handle carrying the static shape.  The handle owns no device memory.
+ * tetri_create checks the configuration (TETRI_ERR_UNSUPPORTED / TETRI_ERR_INVALID_ARG) and
+ * that a HIP device is usable (TETRI_ERR_HIP) and stores the handle in *out.
+ * A handle must not be used by two threads at once.
+ */
+TETRI_API tetri_status tetri_create(const tetri_config *config, tetri_ctx **out);
+TETRI_API void tetri_destroy(tetri_ctx *ctx);
+
+/* Message of the last error on this handle ("" if none).  With ctx == NULL: the message of the
+ * calling thread's last failed tetri_create / tetri_pack_chunks.  Never NULL. */
+TETRI_API const char *tetri_last_error(const tetri_ctx *ctx);
+
+/*
+ * Chunk packing, host only (Sec. 3.3.3 and the prefill-scheduler figure): lay the tokens of
+ * prompts order[0], order[1], ... end to end and cut every chunk_size tokens.  A prompt may be
+ * sliced over several chunks, a chunk may merge several prompts, each request is one contiguous
+ * row range of a chunk; only the last chunk may be short (its remaining rows are padding).
+ *
+ *   prompt_lens [n_prompts] host: token count of each prompt (>= 0; empty prompts are skipped)
+ *   order       [n_order]   host: scheduled order, indices into prompt_lens, no repeats;
+ *                           NULL means 0, 1, ..., n_order - 1 (then n_order <= n_prompts)
+ *   segs        [seg_capacity]           host, out: segments of all chunks, chunk after chunk
+ *   chunk_seg_offsets [chunk_capacity+1] host, out: chunk c owns segs[offsets[c] .. offsets[c+1])
+ *   n_segs_out  host, out (may be NULL): total number of segments
+ * Query mode: with segs == NULL and chunk_seg_offsets == NULL nothing is written except
+ * *n_segs_out; the return value is the number of chunks either way.
+ * Returns the number of chunks (>= 0), or a negative tetri_status: TETRI_ERR_INVALID_ARG
+ * (null prompt_lens, chunk_size < 1, negative length, order entry out of range or repeated),
+ * TETRI_ERR_NOMEM (a capacity is too small; nothing useful is written).
+ */
+TETRI_API int32_t tetri_pack_chunks(const int32_t *prompt_lens, int32_t n_prompts,
+                          const int32_t *order, int32_t n_order, int32_t chunk_size,
+                          tetri_segment *segs, int32_t seg_capacity,
+                          int32_t *chunk_seg_offsets, int32_t chunk_capacity,
+                          int32_t *n_segs_out);
+
+/*
+ * Per-chunk metadata, host only: turn the segments of one chunk into the three int32 arrays
+ * the launching entry points take (the caller then copies them to the device).
+ *   segs [num_segs] host; req_block_tables [n_prompts][max_blocks_per_seq] host: page list of
+ *   every request; cu_out [num_segs+1], ctx_out [num_segs],
+ *   block_table_out [num_segs][max_blocks_per_seq] host, out.
+ * Returns TETRI_OK or TETRI_ERR_INVALID_ARG (null pointer, req out of range, len <= 0).
+ */
+TETRI_API tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t num_segs,
+                                  const int32_t *req_block_tables, int32_t n_prompts,
+                                  int32_t max_blocks_per_seq,
+                                  int32_t *cu_out, int32_t *ctx_out, int32_t *block_table_out);
+
+/*
+ * KV append (Sec. 2.1: prefill generates the KV cache; Sec. 3.4: kept in pages).
+ * For every segment s, local token t < n_s and kv head: copy k_new / v_new[cu[s] + t][head][:]
+ * bit for bit into slot (ctx_lens[s] + t) % page_size of page
+ * block_table[s][(ctx_lens[s] + t) / page_size].  Writes exactly those slots and nothing else;
+ * padding rows are not cached.
+ *   k_new, v_new: device, in.  kv_pages: device, in/out.  block_table, cu_chunk_q_lens,
+ *   ctx_lens: device, in.  num_segs: host scalar, 1..max_segs_per_chunk.
+ */
+TETRI_API tetri_status tetri_kv_append(tetri_ctx *ctx, const void *k_new, const void *v_new, void *kv_pages,
+                             const int32_t *block_table, const int32_t *cu_chunk_q_lens,
+                             const int32_t *ctx_lens, int32_t num_segs, void *stream);
+
+/*
+ * Chunked-prefill attention for one chunk (Sec. 3.3.3: prefill forward one chunk at a time).
+ * Row t of segment s (absolute position p = ctx_lens[s] + t) and query head h produce
+ *     out[cu[s]+t][h][:] = sum_{j=0..p} softmax_j(scale * q[cu[s]+t][h] . K_s[j]) * V_s[j]
+ * where K_s[j], V_s[j] of kv head h / (Hq/Hkv) come from kv_pages through block_table[s] for
+ * j < ctx_lens[s] and from k_new / v_new[cu[s] + j - ctx_lens[s]] otherwise (so the result does
+ * not depend on whether tetri_kv_append has already run for this chunk).  Requests merged into
+ * one chunk never attend to each other; padding rows of `out` are written as +0 and padding
+ * rows of q / k_new / v_new are never read.  Page slots at positions >= ctx_lens[s] are never
+ * read.  Arithmetic: bf16 inputs, fp32 accumulation (bf16 MFMA), online softmax in fp32, the
+ * softmax weights are rounded to bf16 before the PV product, output rounded to bf16 (nearest
+ * even).  Results are deterministic run to run.
+ *   q, k_new, v_new, kv_pages, block_table, cu_chunk_q_lens, ctx_lens: device, in.
+ *   out: device, out.  num_segs, scale: host scalars.
+ */
+TETRI_API tetri_status tetri_chunk_prefill_attn(tetri_ctx *ctx, const void *q, const void *k_new,
+                                      const void *v_new, const void *kv_pages,
+                                      const int32_t *block_table, const int32_t *cu_chunk_q_lens,
+                                      const int32_t *ctx_lens, int32_t num_segs, float scale,
+                                      void *out, void *stream);
+
+/*
+ * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
+ * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
+ * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages
+ * (ceil((ctx+n)/page_size) <= max_blocks_per_seq), and no physical page written by two
+ * segments.  Returns TETRI_OK, TETRI_ERR_INVALID_ARG (message says what), or TETRI_ERR_HIP.
+ */
+TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block_table,
+                                  const int32_t *cu_chunk_q_lens, const int32_t *ctx_lens,
+                                  int32_t num_segs, void *stream);
+
+/*
+ * Kernel-variant selection for measurements.  Known keys: "attn_variant" (0 = default).
+ * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every variant computes the same
+ * function to the same tolerance.
+ */
+TETRI_API tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value);
+
+/* Version of this ABI (bumped on incompatible change). */
+TETRI_API int32_t tetri_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TETRI_H */

@@ -1,0 +1,271 @@
+// Host layer of libtetri: handle, argument checks, the chunk packer and the debug validator.
+// TetriInfer Sec. 3.3.3 "Chunked Prefill" is the source of the packing rule.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tetri_internal.h"
+
+namespace {
+
+thread_local std::string g_thread_err;
+
+tetri_status fail(tetri_ctx *h, tetri_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (h) h->err = buf; else g_thread_err = buf;
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Query-head grouping of a workgroup of 4 wavefronts: the wavefronts of a workgroup are
+// (hpw heads that share a kv head) x (rb blocks of 32 rows).
+void wave_grouping(int g, int *hpw, int *rb)
+{
+    if (g % 4 == 0) *hpw = 4;
+    else if (g == 2) *hpw = 2;
+    else *hpw = 1;
+    *rb = 4 / *hpw;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t tetri_abi_version(void) { return 1; }
+
+const char *tetri_last_error(const tetri_ctx *ctx)
+{
+    return ctx ? ctx->err.c_str() : g_thread_err.c_str();
+}
+
+tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
+{
+    if (!c || !out) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_create: null argument");
+    *out = nullptr;
+    if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads != 0)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_create: num_q_heads=%d must be a positive multiple of num_kv_heads=%d",
+                    c->num_q_heads, c->num_kv_heads);
+    if (c->chunk_size < 1 || c->num_pages < 1 || c->max_blocks_per_seq < 1 || c->max_segs_per_chunk < 1)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_create: chunk_size, num_pages, max_blocks_per_seq and max_segs_per_chunk must be positive");
+    if (c->max_segs_per_chunk > c->chunk_size)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_create: max_segs_per_chunk=%d exceeds chunk_size=%d (segments are non-empty)",
+                    c->max_segs_per_chunk, c->chunk_size);
+    if (c->head_dim != 64 && c->head_dim != 128)
+        return fail(nullptr, TETRI_ERR_UNSUPPORTED, "tetri_create: head_dim=%d (supported: 64, 128)", c->head_dim);
+    if (c->page_size != 16)
+        return fail(nullptr, TETRI_ERR_UNSUPPORTED, "tetri_create: page_size=%d (supported: 16)", c->page_size);
+    if (c->dtype != TETRI_BF16)
+        return fail(nullptr, TETRI_ERR_UNSUPPORTED, "tetri_create: dtype=%d (supported: TETRI_BF16)", c->dtype);
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev < 1)
+        return fail(nullptr, TETRI_ERR_HIP, "tetri_create: no usable HIP device (%s)", e == hipSuccess ? "device count is 0" : hipGetErrorString(e));
+    tetri_ctx *h = new (std::nothrow) tetri_ctx;
+    if (!h) return fail(nullptr, TETRI_ERR_NOMEM, "tetri_create: out of host memory");
+    h->cfg = *c;
+    *out = h;
+    return TETRI_OK;
+}
+
+void tetri_destroy(tetri_ctx *ctx) { delete ctx; }
+
+tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
+{
+    if (!ctx || !key) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: null argument");
+    if (std::strcmp(key, "attn_variant") == 0) {
+        if (value != 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
+        ctx->attn_variant = value;
+        return TETRI_OK;
+    }
+    return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: unknown key '%s'", key);
+}
+
+int32_t tetri_pack_chunks(const int32_t *prompt_lens, int32_t n_prompts, const int32_t *order, int32_t n_order,
+                          int32_t chunk_size, tetri_segment *segs, int32_t seg_capacity,
+                          int32_t *chunk_seg_offsets, int32_t chunk_capacity, int32_t *n_segs_out)
+{
+    if (!prompt_lens || n_prompts < 0 || n_order < 0)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: null prompt_lens or negative count");
+    if (chunk_size < 1) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: chunk_size=%d", chunk_size);
+    if (!order && n_order > n_prompts)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: n_order=%d exceeds n_prompts=%d", n_order, n_prompts);
+    const bool query = (segs == nullptr && chunk_seg_offsets == nullptr);
+    if (!query && (!segs || !chunk_seg_offsets))
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: segs and chunk_seg_offsets must both be given or both be null");
+    std::vector<char> seen(order ? (size_t)n_prompts : 0, 0);
+    int64_t n_chunks = 0, n_segs = 0;
+    int32_t room = 0;                      // free rows left in the chunk being filled
+    for (int32_t i = 0; i < n_order; ++i) {
+        const int32_t req = order ? order[i] : i;
+        if (req < 0 || req >= n_prompts)
+            return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: order[%d]=%d out of range", i, req);
+        if (order) {
+            if (seen[req]) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: request %d scheduled twice", req);
+            seen[req] = 1;
+        }
+        const int32_t len = prompt_lens[req];
+        if (len < 0) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: prompt_lens[%d]=%d", req, len);
+        int32_t done = 0;
+        while (done < len) {
+            if (room == 0) {               // open the next chunk
+                if (!query) {
+                    if (n_chunks >= chunk_capacity)
+                        return fail(nullptr, TETRI_ERR_NOMEM, "tetri_pack_chunks: chunk_capacity=%d too small", chunk_capacity);
+                    chunk_seg_offsets[n_chunks] = (int32_t)n_segs;
+                }
+                ++n_chunks;
+                room = chunk_size;
+            }
+            const int32_t take = (len - done < room) ? len - done : room;
+            if (!query) {
+                if (n_segs >= seg_capacity)
+                    return fail(nullptr, TETRI_ERR_NOMEM, "tetri_pack_chunks: seg_capacity=%d too small", seg_capacity);
+                segs[n_segs].req = req;
+                segs[n_segs].start = done;
+                segs[n_segs].len = take;
+            }
+            ++n_segs;
+            done += take;
+            room -= take;
+        }
+    }
+    if (n_chunks > INT32_MAX || n_segs > INT32_MAX)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: plan too large");
+    if (!query) chunk_seg_offsets[n_chunks] = (int32_t)n_segs;
+    if (n_segs_out) *n_segs_out = (int32_t)n_segs;
+    return (int32_t)n_chunks;
+}
+
+tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t num_segs, const int32_t *req_block_tables,
+                                  int32_t n_prompts, int32_t max_blocks_per_seq,
+                                  int32_t *cu_out, int32_t *ctx_out, int32_t *block_table_out)
+{
+    if (!segs || !req_block_tables || !cu_out || !ctx_out || !block_table_out || num_segs < 1 || max_blocks_per_seq < 1)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_chunk_metadata: null argument or empty chunk");
+    cu_out[0] = 0;
+    for (int32_t s = 0; s < num_segs; ++s) {
+        if (segs[s].req < 0 || segs[s].req >= n_prompts || segs[s].len <= 0 || segs[s].start < 0)
+            return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_chunk_metadata: segment %d is malformed", s);
+        cu_out[s + 1] = cu_out[s] + segs[s].len;
+        ctx_out[s] = segs[s].start;
+        std::memcpy(block_table_out + (size_t)s * max_blocks_per_seq,
+                    req_block_tables + (size_t)segs[s].req * max_blocks_per_seq,
+                    sizeof(int32_t) * (size_t)max_blocks_per_seq);
+    }
+    return TETRI_OK;
+}
+
+static tetri_status check_common(tetri_ctx *h, const char *fn, const void *const *ptrs, const char *const *names, int n,
+                                 int32_t num_segs)
+{
+    if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
+    for (int i = 0; i < n; ++i) {
+        if (!ptrs[i]) return fail(h, TETRI_ERR_INVALID_ARG, "%s: %s is null", fn, names[i]);
+        if (!aligned16(ptrs[i])) return fail(h, TETRI_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", fn, names[i]);
+    }
+    if (num_segs < 1 || num_segs > h->cfg.max_segs_per_chunk)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: num_segs=%d outside 1..%d", fn, num_segs, h->cfg.max_segs_per_chunk);
+    return TETRI_OK;
+}
+
+tetri_status tetri_kv_append(tetri_ctx *h, const void *k_new, const void *v_new, void *kv_pages,
+                             const int32_t *block_table, const int32_t *cu, const int32_t *ctx_lens,
+                             int32_t num_segs, void *stream)
+{
+    const void *ptrs[] = {k_new, v_new, kv_pages};
+    const char *names[] = {"k_new", "v_new", "kv_pages"};
+    tetri_status st = check_common(h, "tetri_kv_append", ptrs, names, 3, num_segs);
+    if (st != TETRI_OK) return st;
+    if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_kv_append: null metadata pointer");
+    AppendParams p;
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.pages = static_cast<uint16_t *>(kv_pages);
+    p.bt = block_table; p.cu = cu; p.ctx = ctx_lens;
+    p.S = num_segs; p.Hkv = h->cfg.num_kv_heads; p.D = h->cfg.head_dim; p.max_blocks = h->cfg.max_blocks_per_seq;
+    hipError_t e = tetri_launch_append(h, p, h->cfg.chunk_size, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "tetri_kv_append: launch failed: %s", hipGetErrorString(e));
+    return TETRI_OK;
+}
+
+tetri_status tetri_chunk_prefill_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                      const void *kv_pages, const int32_t *block_table, const int32_t *cu,
+                                      const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)
+{
+    const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
+    const char *names[] = {"q", "k_new", "v_new", "kv_pages", "out"};
+    tetri_status st = check_common(h, "tetri_chunk_prefill_attn", ptrs, names, 5, num_segs);
+    if (st != TETRI_OK) return st;
+    if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_chunk_prefill_attn: null metadata pointer");
+    if (!std::isfinite(scale)) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_chunk_prefill_attn: scale is not finite");
+    AttnParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.pages = static_cast<const uint16_t *>(kv_pages);
+    p.bt = block_table; p.cu = cu; p.ctx = ctx_lens;
+    p.out = static_cast<uint16_t *>(out);
+    p.S = num_segs; p.C = h->cfg.chunk_size; p.Hq = h->cfg.num_q_heads; p.Hkv = h->cfg.num_kv_heads;
+    p.g = p.Hq / p.Hkv;
+    wave_grouping(p.g, &p.hpw, &p.rb);
+    p.max_blocks = h->cfg.max_blocks_per_seq;
+    p.c = std::fabs(scale) * 1.4426950408889634f;
+    p.neg = scale < 0.f;
+    hipError_t e = tetri_launch_attn(h, p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "tetri_chunk_prefill_attn: launch failed: %s", hipGetErrorString(e));
+    return TETRI_OK;
+}
+
+tetri_status tetri_validate_chunk(tetri_ctx *h, const int32_t *block_table, const int32_t *cu, const int32_t *ctx_lens,
+                                  int32_t num_segs, void *stream)
+{
+    if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: null handle");
+    if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: null metadata pointer");
+    if (num_segs < 1 || num_segs > h->cfg.max_segs_per_chunk)
+        return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: num_segs=%d outside 1..%d", num_segs, h->cfg.max_segs_per_chunk);
+    const tetri_config &c = h->cfg;
+    std::vector<int32_t> hcu((size_t)num_segs + 1), hctx((size_t)num_segs), hbt((size_t)num_segs * c.max_blocks_per_seq);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipMemcpy(hcu.data(), cu, hcu.size() * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(hctx.data(), ctx_lens, hctx.size() * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(hbt.data(), block_table, hbt.size() * 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "tetri_validate_chunk: %s", hipGetErrorString(e));
+    if (hcu[0] != 0) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: cu[0]=%d, expected 0", hcu[0]);
+    std::vector<int32_t> writer((size_t)c.num_pages, -1);
+    for (int32_t s = 0; s < num_segs; ++s) {
+        const int32_t n = hcu[s + 1] - hcu[s];
+        if (n <= 0) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: segment %d has length %d", s, n);
+        if (hctx[s] < 0) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: ctx_lens[%d]=%d", s, hctx[s]);
+        const int64_t end = (int64_t)hctx[s] + n;
+        const int64_t blocks = (end + c.page_size - 1) / c.page_size;
+        if (blocks > c.max_blocks_per_seq)
+            return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: segment %d needs %lld pages, block_table rows hold %d",
+                        s, (long long)blocks, c.max_blocks_per_seq);
+        for (int64_t b = 0; b < blocks; ++b) {
+            const int32_t page = hbt[(size_t)s * c.max_blocks_per_seq + b];
+            if (page < 0 || page >= c.num_pages)
+                return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: block_table[%d][%lld]=%d outside the pool of %d pages",
+                            s, (long long)b, page, c.num_pages);
+            if (b >= hctx[s] / c.page_size) {      // a page this segment writes to
+                if (writer[page] >= 0 && writer[page] != s)
+                    return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: page %d is written by segments %d and %d", page, writer[page], s);
+                writer[page] = s;
+            }
+        }
+    }
+    if (hcu[num_segs] > c.chunk_size)
+        return fail(h, TETRI_ERR_INVALID_ARG, "tetri_validate_chunk: cu[num_segs]=%d exceeds chunk_size=%d", hcu[num_segs], c.chunk_size);
+    return TETRI_OK;
+}
+
+}  // extern "C"

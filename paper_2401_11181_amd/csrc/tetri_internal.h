@@ -1,0 +1,36 @@
+// Internal declarations shared by the host layer and the kernel launchers of libtetri.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "tetri.h"
+
+struct tetri_ctx {
+    tetri_config cfg;
+    std::string err;
+    int attn_variant = 0;
+};
+
+// Launch parameters of the attention kernels (passed by value).
+struct AttnParams {
+    const uint16_t *q, *k_new, *v_new, *pages;   // bf16 bit patterns
+    const int32_t *bt, *cu, *ctx;
+    uint16_t *out;
+    int32_t S, C, Hq, Hkv, g;
+    int32_t hpw;          // query heads handled by one workgroup (they share one kv head)
+    int32_t rb;           // 32-row blocks handled by one workgroup
+    int32_t max_blocks;
+    float c;              // |scale| * log2(e)
+    int32_t neg;          // 1 if scale < 0
+};
+
+struct AppendParams {
+    const uint16_t *k_new, *v_new;
+    uint16_t *pages;
+    const int32_t *bt, *cu, *ctx;
+    int32_t S, Hkv, D, max_blocks;
+};
+
+hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
+hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

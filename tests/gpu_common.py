@@ -1,0 +1,92 @@
+"""GPU-side test plumbing: run a synthetic workload through the C library, chunk by chunk."""
+import numpy as np
+import torch
+
+from oracle import packer as opacker
+from paper_2401_11181_amd import synth
+from paper_2401_11181_amd.prefill import ChunkedPrefill
+
+DEV = "cuda:0"
+
+
+def workload_tensors(w):
+    """Per-request bf16 CPU tensors and block tables of a workload."""
+    qs, ks, vs = [], [], []
+    for r in range(len(w.prompt_lens)):
+        q, k, v = synth.request_qkv(w, r)
+        qs.append(q), ks.append(k), vs.append(v)
+    return qs, ks, vs, synth.place_pages(w)
+
+
+def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False):
+    """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
+    sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                          w.num_pages, tables, device=DEV, page_size=w.page_size)
+    pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
+    dq = [t.to(DEV) for t in qs]
+    dk = [t.to(DEV) for t in ks]
+    dv = [t.to(DEV) for t in vs]
+    outs = [torch.zeros_like(t) for t in qs]
+    chunk_outs = []
+    for c in range(sess.n_chunks):
+        sess.validate(c)
+        q, k, v = sess.gather_chunk(dq, c), sess.gather_chunk(dk, c), sess.gather_chunk(dv, c)
+        segs = sess.chunk_segments(c)
+        n_real = sum(n for _, _, n in segs)
+        if pad_fill is not None and n_real < w.chunk_size:
+            q[n_real:], k[n_real:], v[n_real:] = pad_fill, pad_fill, pad_fill
+        out = torch.full((w.chunk_size, w.num_q_heads, w.head_dim), 7.0, dtype=torch.bfloat16, device=DEV)
+        if append_first:
+            sess.append(c, k, v, pool)
+            sess.attn(c, q, k, v, pool, w.scale, out)
+        else:
+            sess.attn(c, q, k, v, pool, w.scale, out)
+            sess.append(c, k, v, pool)
+        torch.cuda.synchronize()
+        o = out.cpu()
+        at = 0
+        for req, start, n in segs:
+            outs[req][start:start + n] = o[at:at + n]
+            at += n
+        assert not o[n_real:].any(), "padding rows of out must be +0"
+        assert (o[n_real:].view(torch.int16) == 0).all()
+        if keep_chunks:
+            chunk_outs.append(o)
+    return outs, pool, sess, chunk_outs
+
+
+def oracle_prefill(oracle, w, qs, ks, vs, tables):
+    """The same batch through the CPU oracle (float32 data).  Returns (outs, float32 pool)."""
+    pool = np.zeros((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), dtype=np.float32)
+    outs, plan = oracle.prefill([t.float().numpy() for t in qs], [t.float().numpy() for t in ks],
+                                [t.float().numpy() for t in vs], w.order, w.chunk_size, pool, tables, w.scale)
+    return outs, pool, plan
+
+
+def oracle_pool_bits(oracle, w, ks, vs, tables):
+    """The KV pool as bf16 bit patterns after appending every chunk with the oracle."""
+    sent = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), dtype=torch.int16)
+    pool = sent.numpy().view(np.uint16).copy()
+    kb = [t.view(torch.int16).numpy().view(np.uint16) for t in ks]
+    vb = [t.view(torch.int16).numpy().view(np.uint16) for t in vs]
+    max_blocks = max(len(t) for t in tables)
+    for segs in opacker.pack_chunks(w.prompt_lens, w.order, w.chunk_size):
+        cu, ctx = opacker.chunk_arrays(segs)
+        bt = np.zeros((len(segs), max_blocks), dtype=np.int32)
+        for i, (req, _s, _n) in enumerate(segs):
+            bt[i, :len(tables[req])] = tables[req]
+        oracle.kv_append(oracle.gather_chunk(kb, segs, w.chunk_size), oracle.gather_chunk(vb, segs, w.chunk_size),
+                         pool, bt, cu, ctx)
+    return pool
+
+
+def compare(gpu_outs, ref_outs, max_abs=2e-2, mean_abs=2e-3, rel_l2=1e-2, label=""):
+    """spec tolerances: max-abs 2e-2, mean-abs 2e-3 (bf16 inputs, fp32 oracle) + relative L2."""
+    g = np.concatenate([t.float().numpy().reshape(-1) for t in gpu_outs]).astype(np.float64)
+    r = np.concatenate([np.asarray(t).reshape(-1) for t in ref_outs]).astype(np.float64)
+    assert np.isfinite(g).all(), label + ": non-finite GPU output"
+    err = np.abs(g - r)
+    rel = np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-30)
+    stats = dict(max_abs=err.max(), mean_abs=err.mean(), rel_l2=rel)
+    assert err.max() <= max_abs and err.mean() <= mean_abs and rel <= rel_l2, (label, stats)
+    return stats

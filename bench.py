@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked-prefill hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload opt13b] [--mode graph|eager]
+
+One "step" is one pass of the whole hot path over one scheduled batch of synthetic input:
+host chunk packing + per-chunk metadata, one metadata upload, then for every chunk in order one
+attention launch and one KV-append launch (TetriInfer Sec. 3.3.3: prefill one ChunkSize chunk at
+a time).  Q/K/V of every chunk and the page pool are resident in HBM before the timed region.
+Prints ONE JSON line.  `value` = algorithmic attention flops of a step / step time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="opt13b", choices=["tiny", "opt13b", "packed", "heavy", "gqa"])
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2401_11181_amd import synth, tetri
+    from paper_2401_11181_amd.prefill import PrefillPipeline
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = synth.workload(args.workload)
+    tables = synth.place_pages(w)
+    pipe = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                           w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
+                           use_graph=(args.mode == "graph"))
+    if args.variant is not None:
+        pipe.handle.tetri_set_option("attn_variant", args.variant)
+    nC, C = pipe.n_chunks, w.chunk_size
+
+    # inputs: what the QKV projection of each chunk would hand to this path, resident in HBM
+    q = torch.zeros((nC, C, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    k = torch.zeros((nC, C, w.num_kv_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    v = torch.zeros_like(k)
+    out = torch.zeros_like(q)
+    host_reqs = {}
+    for c in range(nC):
+        at = 0
+        for req, start, n in pipe.chunk_segments(c):
+            if req not in host_reqs:
+                host_reqs[req] = synth.request_qkv(w, req)
+            rq, rk, rv = host_reqs[req]
+            q[c, at:at + n] = rq[start:start + n].to(dev)
+            k[c, at:at + n] = rk[start:start + n].to(dev)
+            v[c, at:at + n] = rv[start:start + n].to(dev)
+            at += n
+            if start + n == w.prompt_lens[req] and args.workload in ("packed", "gqa"):
+                del host_reqs[req]
+    pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=dev)
+    pipe.bind(q, k, v, pool, out)
+
+    flops = [pipe.flops(c) for c in range(nC)]
+    total_flops = float(sum(flops))
+
+    # ---- warmup, then exactly K timed steps bracketed by synchronisations
+    for _ in range(args.warmup):
+        pipe.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pipe.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations with HIP events on the launch stream (instrumented eager pass)
+    reps = max(10, min(args.steps, 100))
+    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(nC)] for _ in range(reps)]
+    for r in range(reps):
+        pipe.step(timing=evs[r])
+    torch.cuda.synchronize()
+    attn_ms = np.array([[evs[r][c][0].elapsed_time(evs[r][c][1]) for c in range(nC)] for r in range(reps)])
+    app_ms = np.array([[evs[r][c][1].elapsed_time(evs[r][c][2]) for c in range(nC)] for r in range(reps)])
+    attn_med = np.median(attn_ms, axis=0)
+    app_med = np.median(app_ms, axis=0)
+    attn_avg_ms = float(attn_ms.mean())                 # average duration of one attention launch
+    attn_flops_per_launch = total_flops / nC
+    achieved_tflops = attn_flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
+    app_bytes = float(np.mean([pipe.append_bytes(c) for c in range(nC)]))
+    app_avg_ms = float(app_ms.mean())
+
+    result = {
+        "metric": "chunked_prefill_attention_tflops",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_chunk": round(ms_per_step / nC, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: %d prompt(s), %d tokens, %d chunks of ChunkSize %d, %dx%d query heads, %d kv heads, "
+                        "page size %d, causal, seed %d" % (w.name, len(w.prompt_lens), sum(w.prompt_lens), nC, C,
+                                                           w.num_q_heads, w.head_dim, w.num_kv_heads, w.page_size,
+                                                           w.seed),
+            "chunk_size": C, "launch_mode": args.mode,
+            "step": "pack + metadata + upload + per chunk (attention, kv append)",
+        },
+        "roofline": {
+            "bound": "mfma", "kernel": "attn_fwd_kernel",
+            "achieved": round(achieved_tflops, 3), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved_tflops / PEAK_BF16_MFMA_TFLOPS, 5),
+            "avg_launch_ms": round(attn_avg_ms, 5), "flops_per_launch": attn_flops_per_launch,
+            "traffic": None,
+        },
+        "per_chunk": {
+            "attn_ms_median": [round(float(x), 5) for x in attn_med[:64]],
+            "attn_tflops": [round(flops[c] / (float(attn_med[c]) * 1e-3) / 1e12, 2) for c in range(min(nC, 64))],
+            "append_ms_median": [round(float(x), 5) for x in app_med[:64]],
+        },
+        "append": {"avg_launch_ms": round(app_avg_ms, 5),
+                   "achieved_GBs": round(app_bytes / (app_avg_ms * 1e-3) / 1e9, 1), "peak_GBs": PEAK_HBM_GBS,
+                   "frac": round(app_bytes / (app_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+
+    # ---- the CPU oracle on the host cores of this machine (reported baseline, not the target)
+    if not args.no_cpu_baseline:
+        from oracle import tetri_oracle
+        from oracle import packer as opacker
+        lib = tetri_oracle.load()
+        threads = os.cpu_count() or 1
+        try:
+            import ctypes
+            omp = ctypes.CDLL("libgomp.so.1")
+            threads = int(omp.omp_get_max_threads())
+        except OSError:
+            pass
+        # bounded sample: whole chunks of the same workload until about 10 s of CPU work
+        plan = opacker.pack_chunks(w.prompt_lens, w.order, C)
+        opool = np.zeros((w.num_pages if w.num_pages <= 4096 else 1, 2, w.num_kv_heads, w.page_size, w.head_dim),
+                         dtype=np.float32)
+        sample_flops, cpu_s, n_done, worst = 0.0, 0.0, 0, 0.0
+        out_host = out.float().cpu().numpy()
+        if w.num_pages <= 4096:
+            qh, kh, vh = q.float().cpu().numpy(), k.float().cpu().numpy(), v.float().cpu().numpy()
+            max_blocks = max(len(t) for t in tables)
+            for c, segs in enumerate(plan):
+                cu, ctx = opacker.chunk_arrays(segs)
+                bt = np.zeros((len(segs), max_blocks), dtype=np.int32)
+                for i, (req, _s, _n) in enumerate(segs):
+                    bt[i, :len(tables[req])] = tables[req]
+                ts = time.perf_counter()
+                o = tetri_oracle.chunk_prefill_attn(qh[c], kh[c], vh[c], opool, bt, cu, ctx, w.scale, lib=lib)
+                tetri_oracle.kv_append(kh[c], vh[c], opool, bt, cu, ctx, lib=lib)
+                cpu_s += time.perf_counter() - ts
+                sample_flops += flops[c]
+                n_done += 1
+                worst = max(worst, float(np.abs(o - out_host[c]).max()))
+                if cpu_s > 10.0:
+                    break
+            result["cpu_baseline"] = {
+                "value": round(sample_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
+                "kind": "oracle", "seconds": round(cpu_s, 3),
+                "sample": "chunks 0..%d of %d of the same workload (attention + append), all heads" % (n_done - 1, nC),
+            }
+            result["parity_check"] = {"max_abs_vs_oracle": round(worst, 6), "chunks": n_done}
+        else:
+            result["cpu_baseline"] = None
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -9,7 +9,7 @@
 struct tetri_ctx {
     tetri_config cfg;
     std::string err;
-    int attn_variant = 0;
+    int attn_variant = 0;   // 0 = choose by grid size, 1 = 4-wave workgroups, 2 = 2-wave workgroups
 };
 
 // Launch parameters of the attention kernels (passed by value).
@@ -21,6 +21,7 @@ struct AttnParams {
     int32_t hpw;          // query heads handled by one workgroup (they share one kv head)
     int32_t rb;           // 32-row blocks handled by one workgroup
     int32_t max_blocks;
+    int32_t tiles;        // upper bound of the number of row tiles of the chunk
     float c;              // |scale| * log2(e)
     int32_t neg;          // 1 if scale < 0
 };

@@ -178,8 +178,8 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
                                   int32_t num_segs, void *stream);
 
 /*
- * Kernel-variant selection for measurements.  Known keys: "attn_variant" (0 = choose the
- * workgroup shape from the grid size, 1 = 4-wavefront workgroups, 2 = 2-wavefront workgroups).
+ * Kernel-variant selection for measurements.  Known keys: "attn_variant" (0 = the library chooses the
+ * kernel, 1 / 2 = shared-tile kernel with 4- / 8-wavefront workgroups, 3 = key-split kernel).
  * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every variant computes the same
  * function to the same tolerance.
  */

@@ -1,0 +1,119 @@
+// Device helpers shared by the attention kernels of libtetri (gfx950 only).
+#pragma once
+#include "tetri_internal.h"
+
+namespace tetri_dev {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_cvoid;
+
+constexpr int kPage = 16;     // tokens per KV page
+constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
+
+// A row of zeros: out-of-range key rows of a partial tile are loaded from here.
+static __device__ __attribute__((aligned(256))) uint4 g_zero_row[16];
+
+template <int D> __device__ __forceinline__ int k_swizzle(int row)
+{
+    // 16 consecutive rows must land in 16 different 16-byte bank groups
+    return (D == 128) ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D> __device__ __forceinline__ int v_swizzle(int row)
+{
+    // 4 consecutive rows x 64 contiguous bytes must land in 4 different 64-byte bank groups
+    return (D == 128) ? ((row & 3) << 2) : (((row ^ (row >> 1)) & 1) << 2);
+}
+
+// Exchange between the two half-waves (lanes l and l^32 hold the same query) with
+// v_permlane32_swap: afterwards the first register holds, in every lane, the value of the lower
+// half-wave and the second the value of the upper half-wave.  Written as inline assembly because
+// the compiler builtin returned its first result for both elements when both were consumed by
+// one arithmetic instruction; the s_nop cover the VALU-write -> permlane-swap wait states.
+__device__ __forceinline__ void half_swap(float x, float &lo_half, float &hi_half)
+{
+    int a = __builtin_bit_cast(int, x), b = a;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    lo_half = __builtin_bit_cast(float, a);
+    hi_half = __builtin_bit_cast(float, b);
+}
+__device__ __forceinline__ float half_swap_max(float x)
+{
+    float a, b;
+    half_swap(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_swap_sum(float x)
+{
+    float a, b;
+    half_swap(x, a, b);
+    return a + b;
+}
+
+
+// Direct global -> LDS load of 16 bytes per lane, issued from inline assembly: lane l's 16 bytes
+// land at LDS byte address lds_base + 16*l (lds_base is wave-uniform and goes to M0).  The
+// compiler does not see this as a memory access, so it inserts no waits for it: the caller
+// orders it with wait_vm<N>() below.  (The compiler's own tracking of such loads cannot tell
+// apart two buffers that are slices of one array and falls back to waiting for everything.)
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+// Same, with the global address given as a wave-uniform 64-bit base plus a per-lane 32-bit byte
+// offset (no per-lane 64-bit address arithmetic).
+__device__ __forceinline__ void dma16_sbase(const void *sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+// Wait until at most N vector-memory operations of this wavefront are outstanding; also a
+// compiler barrier for memory accesses, so LDS reads stay behind it.
+template <int N> __device__ __forceinline__ void wait_vm()
+{
+    static_assert(N == 0 || N == 4 || N == 8, "unsupported count");
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+// Everything a wavefront needs to know about where its workgroup's keys come from.
+struct KeySource {
+    const uint16_t *pages, *k_new, *v_new;
+    const int32_t *bt_row;
+    int Hkv, kh, row_base, L, n_new, n_ctx_tiles, max_blocks;
+};
+
+// The block table is read-only for the whole launch, so its (wave-uniform) entries are read
+// through the constant address space: the compiler then uses scalar loads and the page ids live
+// in SGPRs, off the vector-memory queue that carries the K/V tiles.
+typedef __attribute__((address_space(4))) const int32_t const_i32;
+
+// Physical pages of the (up to 4) logical pages of context tile `it` (unused for new-token
+// tiles).  Plain scalars, not an array, so that they stay in SGPRs.
+struct TilePages { int p0, p1, p2, p3; };
+
+template <int BN>
+__device__ __forceinline__ TilePages load_tile_pages(const KeySource &ks, int it)
+{
+    const const_i32 *bt = (const const_i32 *)(uintptr_t)ks.bt_row;
+    const int first = it * (BN / kPage), last = ks.max_blocks - 1;   // clamped entries are never used
+    TilePages tp;
+    tp.p0 = bt[min(first, last)];
+    tp.p1 = bt[min(first + 1, last)];
+    tp.p2 = BN > 32 ? bt[min(first + 2, last)] : 0;
+    tp.p3 = BN > 32 ? bt[min(first + 3, last)] : 0;
+    return tp;
+}
+
+
+}  // namespace tetri_dev

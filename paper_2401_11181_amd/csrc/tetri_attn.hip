@@ -1,16 +1,20 @@
-// Chunked-prefill causal attention over a paged KV cache for gfx950 (CDNA4).
+// Chunked-prefill causal attention over a paged KV cache for gfx950 (CDNA4): shared-tile kernel.
 // TetriInfer Sec. 3.3.3 (prefill one fixed-size chunk at a time; several requests may be merged
 // into a chunk), Sec. 2.1 (causal prefill), Sec. 3.4 (paged KV).  The kernel is a flash-style
 // single pass with online softmax; that structure is prior art (the paper names FlashAttention
 // as orthogonal work), the paper itself gives no kernel.
 //
 // Mapping to the hardware
-//   * A workgroup is NW wavefronts of 64 lanes.  A wavefront owns 32 query rows of one query
-//     head; the wavefronts of a workgroup are (heads sharing one kv head) x (32-row blocks), so a
-//     K/V tile staged in LDS is used by all of them.
-//   * K/V tiles (64 or 32 keys) go from HBM/L2 straight into LDS with global_load_lds_dwordx4 (no
-//     register staging), double buffered: the loads of tile i+1 are in flight while tile i is
-//     consumed; one workgroup barrier per tile.
+//   * A workgroup is 4*KS wavefronts.  A wavefront owns 32 query rows of one query head and one
+//     of KS parts of every key stage; the 4 row/head slots are (heads sharing one kv head) x
+//     (32-row blocks).  With KS = 2 a CU holds 8 wavefronts, two per SIMD, so one wavefront's
+//     softmax (VALU) overlaps the other's MFMA, while every K/V byte brought into LDS still
+//     serves 128 query rows.  The KS partial results are merged once through LDS at the end.
+//   * A stage is 64*KS keys of K and V.  Stages go from HBM/L2 straight into LDS with
+//     global_load_lds_dwordx4 (no register staging), double buffered: the loads of stage i+1 are
+//     in flight while stage i is consumed; one workgroup barrier per stage.  The 16 key rows a
+//     wavefront loads per stage are exactly one (page, kv head) block of the pool, 4 KB
+//     contiguous: one scalar base address per block, per-lane offsets fixed for the whole kernel.
 //   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: K fragments
 //     come from LDS (A operand), Q fragments stay in registers (B operand).  In the accumulator
 //     layout every lane then holds 16 keys of ONE query, so row max / row sum are in-lane
@@ -23,138 +27,116 @@
 //     global address of the direct load) so that the 128-bit K reads and the transposing V reads
 //     are bank-conflict free.
 //   * Workgroup ids are remapped so that all row tiles of a kv head run on one XCD (one L2).
-#include "tetri_internal.h"
+#include "attn_common.h"
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_cvoid;
+using namespace tetri_dev;
 
-constexpr int kPage = 16;     // tokens per KV page
-constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
+constexpr int kSlots = 4;     // (head, 32-row block) slots of a workgroup
+constexpr int kBNW = 64;      // keys per wavefront per stage
 
-// A row of zeros: out-of-range key rows of a partial tile are loaded from here.
-__device__ __attribute__((aligned(256))) uint4 g_zero_row[16];
-
-template <int D> __device__ __forceinline__ int k_swizzle(int row)
-{
-    // 16 consecutive rows must land in 16 different 16-byte bank groups
-    return (D == 128) ? (row & 15) : ((row >> 1) & 7);
-}
-template <int D> __device__ __forceinline__ int v_swizzle(int row)
-{
-    // 4 consecutive rows x 64 contiguous bytes must land in 4 different 64-byte bank groups
-    return (D == 128) ? ((row & 3) << 2) : (((row ^ (row >> 1)) & 1) << 2);
-}
-
-// Exchange between the two half-waves (lanes l and l^32 hold the same query) with
-// v_permlane32_swap: afterwards the first register holds, in every lane, the value of the lower
-// half-wave and the second the value of the upper half-wave.  Written as inline assembly because
-// the compiler builtin returned its first result for both elements when both were consumed by
-// one arithmetic instruction; the s_nop cover the VALU-write -> permlane-swap wait states.
-__device__ __forceinline__ void half_swap(float x, float &lo_half, float &hi_half)
-{
-    int a = __builtin_bit_cast(int, x), b = a;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-    lo_half = __builtin_bit_cast(float, a);
-    hi_half = __builtin_bit_cast(float, b);
-}
-__device__ __forceinline__ float half_swap_max(float x)
-{
-    float a, b;
-    half_swap(x, a, b);
-    return fmaxf(a, b);
-}
-__device__ __forceinline__ float half_swap_sum(float x)
-{
-    float a, b;
-    half_swap(x, a, b);
-    return a + b;
-}
-
-// Everything a wavefront needs to know about where its workgroup's keys come from.
-struct KeySource {
-    const uint16_t *pages, *k_new, *v_new;
-    const int32_t *bt_row;
-    int Hkv, kh, row_base, L, n_new, n_ctx_tiles, max_blocks;
+// Per-lane byte offsets of a wavefront's loads, fixed for the whole kernel.
+// A wavefront loads 16 key rows per stage with NI = 4 (head_dim 128) or 2 (head_dim 64)
+// instructions of 1 KB; lane l of instruction i lands at LDS byte 1024*i + 16*l, i.e. row
+// r = RPI*i + l/CH of the wavefront's 16 rows, chunk position l%CH, and therefore fetches chunk
+// (l%CH) ^ swizzle(r) of that row.  RPI*i only touches swizzle bits that l/CH leaves free, so
+// instruction i's offset is instruction 0's offset with a constant XOR-ed in, plus i row groups.
+template <int D>
+struct LaneOffsets {
+    uint32_t k_ctx, v_ctx;      // rows 512 (256) bytes apart inside a (page, head) block of the pool
+    uint32_t k_new, v_new;      // rows Hkv*D*2 bytes apart in k_new / v_new
 };
 
-// The block table is read-only for the whole launch, so its (wave-uniform) entries are read
-// through the constant address space: the compiler then uses scalar loads and the page ids live
-// in SGPRs, off the vector-memory queue that carries the K/V tiles.
-typedef __attribute__((address_space(4))) const int32_t const_i32;
-
-// Physical pages of the (up to 4) logical pages of context tile `it` (unused for new-token
-// tiles).  Plain scalars, not an array, so that they stay in SGPRs.
-struct TilePages { int p0, p1, p2, p3; };
-
-template <int BN>
-__device__ __forceinline__ TilePages load_tile_pages(const KeySource &ks, int it)
-{
-    const const_i32 *bt = (const const_i32 *)(uintptr_t)ks.bt_row;
-    const int first = it * (BN / kPage), last = ks.max_blocks - 1;   // clamped entries are never used
-    TilePages tp;
-    tp.p0 = bt[min(first, last)];
-    tp.p1 = bt[min(first + 1, last)];
-    tp.p2 = BN > 32 ? bt[min(first + 2, last)] : 0;
-    tp.p3 = BN > 32 ? bt[min(first + 3, last)] : 0;
-    return tp;
-}
-
-// Issue the direct-to-LDS loads of this wavefront's share of tile `it` (K and V, BN keys).
-// One instruction moves 1 KB = 4 key rows (8 for head_dim 64); lane l lands at byte 16*l of that
-// KB, so it fetches row 4q + l/16, 16-byte chunk (l%16) ^ swizzle(row).
-template <int D, int NW, int BN>
-__device__ __forceinline__ void issue_tile_loads(const KeySource &ks, const TilePages &tp, int it, int wave, int lane,
-                                                 uint4 *Kbuf, uint4 *Vbuf)
+template <int D>
+__device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane, int new_row_bytes)
 {
     constexpr int CH = D / 8;
-    constexpr int ROWS_PER_INST = 64 / CH;             // 4 for D=128, 8 for D=64
-    constexpr int INSTS = BN / ROWS_PER_INST;          // per matrix per tile
-    constexpr int PER_WAVE = INSTS / NW;
+    const int r0 = lane / CH;                                    // row of instruction 0
+    const int kc = (lane % CH) ^ k_swizzle<D>(r0);
+    const int vc = (lane % CH) ^ v_swizzle<D>(r0);
+    lo.k_ctx = r0 * D * 2 + kc * 16;
+    lo.v_ctx = r0 * D * 2 + vc * 16;
+    lo.k_new = r0 * new_row_bytes + kc * 16;
+    lo.v_new = r0 * new_row_bytes + vc * 16;
+}
+// XOR that turns instruction 0's chunk into instruction i's (in bytes).
+template <int D> __device__ __forceinline__ constexpr uint32_t k_inst_xor(int i)
+{
+    return (uint32_t)(k_swizzle<D>((64 / (D / 8)) * i) * 16);
+}
+template <int D> __device__ __forceinline__ constexpr uint32_t v_inst_xor(int i)
+{
+    return (uint32_t)(v_swizzle<D>((64 / (D / 8)) * i) * 16);
+}
+
+// Issue the direct-to-LDS loads of this wavefront's 16 rows of stage `it` (K and V).
+template <int D, int KS>
+__device__ __forceinline__ void issue_stage_loads(const KeySource &ks, const LaneOffsets<D> &lo, int page, int it,
+                                                  int wave, int lane, int new_row_bytes, uint32_t k_lds, uint32_t v_lds)
+{
+    constexpr int CH = D / 8, RPI = 64 / CH, NI = 16 / RPI;
+    constexpr int STAGE = kBNW * KS;
     const bool is_ctx = it < ks.n_ctx_tiles;
-    const int base = (is_ctx ? it : it - ks.n_ctx_tiles) * BN;
+    const int base = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE;
     const int limit = is_ctx ? ks.L : ks.n_new;
-    const size_t head_block = (size_t)kPage * D;
-    const int lr = lane / CH, cpos = lane % CH;
-    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_zero_row);
+    const int j0 = base + 16 * wave;                             // first key row of this wavefront
+    const uint32_t kdst = k_lds + wave * (16 * D * 2), vdst = v_lds + wave * (16 * D * 2);
+    // wave-uniform base addresses of row j0 and the distance between row groups of two instructions
+    const char *kb, *vb;
+    int inst_bytes;
+    if (is_ctx) {
+        kb = reinterpret_cast<const char *>(ks.pages) + ((size_t)page * 2 * ks.Hkv + ks.kh) * (size_t)(kPage * D * 2);
+        vb = kb + (size_t)ks.Hkv * (kPage * D * 2);
+        inst_bytes = RPI * D * 2;
+    } else {
+        const size_t off = ((size_t)(ks.row_base + j0) * ks.Hkv + ks.kh) * (size_t)(D * 2);
+        kb = reinterpret_cast<const char *>(ks.k_new) + off;
+        vb = reinterpret_cast<const char *>(ks.v_new) + off;
+        inst_bytes = RPI * new_row_bytes;
+    }
+    const uint32_t ko = is_ctx ? lo.k_ctx : lo.k_new, vo = is_ctx ? lo.v_ctx : lo.v_new;
+    if (j0 + 16 <= limit) {
+        // all 16 rows exist: scalar base + per-lane offset
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
-        const int q = wave * PER_WAVE + i;             // wave-uniform
-        const int r = q * ROWS_PER_INST + lr;          // row inside the tile
-        const int j = base + r;
-        // the rows of one instruction lie inside one 16-token page
-        const int pk = (q * ROWS_PER_INST) / kPage;    // wave-uniform
-        const int page = pk == 0 ? tp.p0 : pk == 1 ? tp.p1 : pk == 2 ? tp.p2 : tp.p3;
-        const uint16_t *kctx = ks.pages + ((size_t)page * 2 * ks.Hkv + ks.kh) * head_block + (size_t)(j % kPage) * D;
-        const size_t noff = ((size_t)(ks.row_base + j) * ks.Hkv + ks.kh) * D;
-        const uint16_t *ksrc = is_ctx ? kctx : ks.k_new + noff;
-        const uint16_t *vsrc = is_ctx ? kctx + (size_t)ks.Hkv * head_block : ks.v_new + noff;
-        const bool ok = j < limit;
-        const uint16_t *kp = ok ? ksrc + ((cpos ^ k_swizzle<D>(r)) << 3) : zero;
-        const uint16_t *vp = ok ? vsrc + ((cpos ^ v_swizzle<D>(r)) << 3) : zero;
-        __builtin_amdgcn_global_load_lds((gbl_cvoid *)kp, (lds_void *)(Kbuf + q * 64), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_cvoid *)vp, (lds_void *)(Vbuf + q * 64), 16, 0, 0);
+        for (int i = 0; i < NI; ++i) {
+            dma16_sbase(kb + (size_t)i * inst_bytes, ko ^ k_inst_xor<D>(i), kdst + 1024 * i);
+            dma16_sbase(vb + (size_t)i * inst_bytes, vo ^ v_inst_xor<D>(i), vdst + 1024 * i);
+        }
+    } else {
+        // ragged end of the key range: rows past the limit come from a row of zeros
+        const char *zero = reinterpret_cast<const char *>(g_zero_row);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const bool ok = j0 + RPI * i + lane / CH < limit;
+            dma16(ok ? kb + (size_t)i * inst_bytes + (ko ^ k_inst_xor<D>(i)) : zero, kdst + 1024 * i);
+            dma16(ok ? vb + (size_t)i * inst_bytes + (vo ^ v_inst_xor<D>(i)) : zero, vdst + 1024 * i);
+        }
     }
 }
 
-template <int D, int NW, int BN>
-__global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
+template <int KS>
+__device__ __forceinline__ int load_stage_page(const KeySource &ks, int it, int wave)
+{
+    const const_i32 *bt = (const const_i32 *)(uintptr_t)ks.bt_row;
+    return bt[min(it * (kBNW * KS / kPage) + wave, ks.max_blocks - 1)];   // clamped entries are never used
+}
+
+template <int D, int KS>
+__global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
 {
     constexpr int CH = D / 8;        // 16-byte chunks per K/V row
     constexpr int KSTEPS = D / 16;   // MFMA steps over d for S^T
     constexpr int DBLK = D / 32;     // 32-row blocks of O^T
-    constexpr int NKB = BN / 32;     // 32-key blocks of S^T per tile
-    __shared__ uint4 Ks0[BN * CH], Ks1[BN * CH], Vs0[BN * CH], Vs1[BN * CH];
+    constexpr int NKB = kBNW / 32;   // 32-key blocks of S^T per wavefront per stage
+    constexpr int STAGE = kBNW * KS; // keys per stage
+    constexpr int STAGE_U4 = STAGE * CH;
+    __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stages: K0 | V0 | K1 | V1
+    __shared__ float Mstat[kSlots][2][32];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slot = wave % kSlots, kq = wave / kSlots;    // row/head slot, key part
     const int half = lane >> 5, l32 = lane & 31;
     const int BM = 32 * p.rb;
     const int S = p.S;
@@ -175,12 +157,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
         if (tile < nt) { t0 = tile * BM; break; }
         tile -= nt;
     }
-    const int hh = wave % p.hpw, rbk = wave / p.hpw;
+    const int hh = slot % p.hpw, rbk = slot / p.hpw;
     const int head = grp * p.hpw + hh;
     if (t0 < 0) {
         // padding rows [cu[S], C): written as +0
         const int r0 = p.cu[S] + tile * BM + 32 * rbk;
-        if (r0 >= p.C) return;
+        if (r0 >= p.C || kq != 0) return;
         const int r = r0 + l32;
         if (r < p.C) {
             uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + head) * D);
@@ -194,18 +176,24 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
     ks.bt_row = p.bt + (size_t)s * p.max_blocks;
     ks.Hkv = p.Hkv; ks.kh = (grp * p.hpw) / p.g; ks.row_base = p.cu[s]; ks.L = L;
     ks.n_new = min(n_s, t0 + BM);                      // new keys any row of this tile may see
-    ks.n_ctx_tiles = (L + BN - 1) / BN;
+    ks.n_ctx_tiles = (L + STAGE - 1) / STAGE;
     ks.max_blocks = p.max_blocks;
-    const int n_tiles = ks.n_ctx_tiles + (ks.n_new + BN - 1) / BN;
+    const int n_stages = ks.n_ctx_tiles + (ks.n_new + STAGE - 1) / STAGE;
 
     const int tw0 = t0 + 32 * rbk;         // first local row of this wavefront
     const int t = tw0 + l32;               // local row of this lane's query
     const bool row_ok = t < n_s;
     const bool wave_has_rows = tw0 < n_s;
 
-    TilePages tp = load_tile_pages<BN>(ks, 0);
-    issue_tile_loads<D, NW, BN>(ks, tp, 0, wave, lane, Ks0, Vs0);
-    tp = load_tile_pages<BN>(ks, 1);
+    const int new_row_bytes = p.Hkv * D * 2;
+    LaneOffsets<D> lo;
+    init_lane_offsets<D>(lo, lane, new_row_bytes);
+    const uint32_t smem_lds = lds_address(smem);
+    constexpr uint32_t STAGE_BYTES = STAGE_U4 * 16;   // bytes of one matrix of one stage
+
+    int page = load_stage_page<KS>(ks, 0, wave);
+    issue_stage_loads<D, KS>(ks, lo, page, 0, wave, lane, new_row_bytes, smem_lds, smem_lds + STAGE_BYTES);
+    page = load_stage_page<KS>(ks, 1, wave);
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7]
     bf16x8 qf[KSTEPS];
@@ -214,6 +202,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st) {
             uint4 v = row_ok ? qp[2 * st + half] : make_uint4(0, 0, 0, 0);
+            if (p.neg) {         // a negative scale is applied as |scale| to -q (exact in bf16)
+                v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
+            }
             qf[st] = __builtin_bit_cast(bf16x8, v);
         }
     }
@@ -226,78 +217,22 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
     float m = -1e30f;        // running row max (in units of log2: score * c)
     float lsum = 0.f;        // this lane's share of the running row sum
     const float c = p.c;
+    const int blk = lane >> 4, i16 = lane & 15;
 
-    auto consume = [&](int it, const uint4 *Kt, const uint4 *Vt) {
-        const bool is_ctx = it < ks.n_ctx_tiles;
-        const int base = (is_ctx ? it : it - ks.n_ctx_tiles) * BN;
-        // a wavefront whose rows all precede this tile's keys has nothing to do here
-        if (!(wave_has_rows && (is_ctx || base <= tw0 + 31))) return;
-
-        // ---- S^T = K Q^T for BN keys x 32 queries
-        f32x16 sacc[NKB];
+    // Fragment loads from LDS.  K: lane holds key row0 + l32, d = 16*st + 8*half .. +7 (A operand
+    // of S^T).  V: for step j (16 keys) and d block db the lane gets keys row0 + 16j + 4*half +
+    // {0..3, 8..11} of d = 32*db + l32 through two transposing reads (A operand of O^T).
+    auto load_k = [&](bf16x8 (&kf)[KSTEPS], int row0, const uint4 *Kt) {
+        const int r = row0 + l32;
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
-            const int r = kb * 32 + l32;
-#pragma unroll
-            for (int st = 0; st < KSTEPS; ++st) {
-                const uint4 kq = Kt[r * CH + ((2 * st + half) ^ k_swizzle<D>(r))];
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kq), qf[st], sacc[kb], 0, 0, 0);
-            }
-        }
-        if (p.neg) {
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sacc[kb][v] = -sacc[kb][v];
-        }
-        // ---- mask: accumulator element v of block kb is key base + kb*32 + (v/4)*8 + 4*half + v%4
-        const bool need_mask = is_ctx ? (base + BN > L) : (base + BN - 1 > tw0);
-        if (need_mask) {
-            const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = base + kb * 32 + (v / 4) * 8 + 4 * half + (v % 4);
-                    if (key > bound) sacc[kb][v] = -INFINITY;
-                }
-        }
-        // ---- online softmax (per query = per lane pair)
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
-        mx = half_swap_max(mx);
-        const float m_new = fmaxf(m, mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        lsum *= alpha;
-        bf16x8 pf[2 * NKB];
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][v], c, -m_new));
-                if (need_mask && sacc[kb][v] == -INFINITY) pv = 0.f;   // also right for scale == 0
-                lsum += pv;
-                pf[kb * 2 + v / 8][v % 8] = (__bf16)pv;
-            }
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-            for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
-        }
-        // ---- O^T += V^T P^T.  Step kj contracts the 16 keys held in accumulator elements
-        // 8j..8j+7 of block kb (kj = 2*kb + j): rows 16*kj + 4*half + {0..3} and the same + 8.
-        const int blk = lane >> 4, i16 = lane & 15;
+        for (int st = 0; st < KSTEPS; ++st)
+            kf[st] = __builtin_bit_cast(bf16x8, Kt[r * CH + ((2 * st + half) ^ k_swizzle<D>(r))]);
+    };
+    auto load_v = [&](s16x8 (&vf)[2 * DBLK], int row0, const uint4 *Vt) {
         const char *vb = reinterpret_cast<const char *>(Vt);
 #pragma unroll
-        for (int kj = 0; kj < 2 * NKB; ++kj) {
-            const int ra = kj * 16 + 4 * half + (i16 >> 2), rb2 = ra + 8;
+        for (int j = 0; j < 2; ++j) {
+            const int ra = row0 + j * 16 + 4 * half + (i16 >> 2), rb2 = ra + 8;
 #pragma unroll
             for (int db = 0; db < DBLK; ++db) {
                 const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
@@ -305,31 +240,144 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
                 const int offb = rb2 * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rb2)) << 4) + ((d0 & 7) << 1);
                 const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vb + offa));
                 const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vb + offb));
-                const s16x8 v8 = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pf[kj], o[db], 0, 0, 0);
+                vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
 
-    // ---- main loop, two tiles per trip so that each LDS buffer is named statically.  `tp` always
-    // holds the page ids of the tile whose loads are issued next; they are fetched one tile ahead.
-    for (int it = 0; it < n_tiles; it += 2) {
-        __builtin_amdgcn_s_waitcnt(0);      // this wavefront's loads of tile `it` have landed
+    // One 32-key block for this wavefront: keys key0 .. key0+31 at rows row0 .. row0+31 of the stage
+    // buffers; its K fragments are already in kf.  If next_row0 >= 0 the K fragments of the block at
+    // that row are fetched into kf while the PV product runs.  The running max / sum / O are
+    // updated per block (online softmax); the max is only raised when a row's block maximum
+    // exceeds it by more than 2^8, so weights stay below 2^8 and O is rescaled rarely.
+    auto consume = [&](bool need_mask, int bound, int key0, int row0, int next_row0, bf16x8 (&kf)[KSTEPS],
+                       const uint4 *Kt, const uint4 *Vt) {
+        // ---- S^T = K Q^T for 32 keys x 32 queries
+        f32x16 sacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st)
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qf[st], sacc, 0, 0, 0);
+        // V fragments of this block travel from LDS while the scores are computed and exponentiated
+        s16x8 vf[2 * DBLK];
+        load_v(vf, row0, Vt);
+        // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
+        // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
+        if (need_mask) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
+                if (key > bound) sacc[v] = -INFINITY;
+            }
+        }
+        // ---- online softmax (per query = per lane pair)
+        float mx = sacc[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
+        mx = half_swap_max(mx) * c;
+        if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
+            const float m_new = fmaxf(m, mx);
+            float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            // the wait state a transcendental result needs before a VALU use; the compiler does not
+            // insert it in front of inline assembly
+            asm volatile("s_nop 1" : "+v"(alpha));
+            m = m_new;
+            lsum *= alpha;
+            // in place, so that the accumulators keep their registers on both paths
+#pragma unroll
+            for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(o[i][v]) : "v"(alpha));
+        }
+        bf16x8 pf[2];
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+            bf16x2 pp;
+            pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], c, -m));
+            pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v + 1], c, -m));
+            // the row sum is taken over the rounded weights, the ones the PV product uses
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
+            pf[v / 8][v % 8] = pp[0];
+            pf[v / 8][v % 8 + 1] = pp[1];
+        }
+        // K fragments of the next block travel while the PV product runs
+        if (next_row0 >= 0) load_k(kf, next_row0, Kt);
+        // ---- O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
+    };
+
+    auto stage = [&](int it, const uint4 *Kt, const uint4 *Vt) {
+        if (!wave_has_rows) return;
+        const bool is_ctx = it < ks.n_ctx_tiles;
+        const int part0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW;   // first key of this wavefront's part
+        // active blocks (a prefix of the part): inside the key range and not past this wavefront's rows
+        int nblk = 0;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            const int key0 = part0 + kb * 32;
+            if (is_ctx ? key0 < L : (key0 < ks.n_new && key0 <= tw0 + 31)) nblk = kb + 1;
+        }
+        if (nblk == 0) return;
+        const int bound = is_ctx ? L - 1 : t;          // last visible key index of this phase
+        bf16x8 kf[KSTEPS];
+        load_k(kf, kq * kBNW, Kt);
+#pragma unroll 1
+        for (int kb = 0; kb < nblk; ++kb) {
+            const int key0 = part0 + kb * 32;
+            const int row0 = kq * kBNW + kb * 32;
+            const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
+            consume(need_mask, bound, key0, row0, (kb + 1 < nblk) ? row0 + 32 : -1, kf, Kt, Vt);
+        }
+    };
+
+    // ---- main loop.  `page` always belongs to the stage whose loads are issued next; it is
+    // fetched one stage ahead.
+    for (int it = 0; it < n_stages; ++it) {
+        const int cur = it & 1;
+        wait_vm<0>();                       // this wavefront's loads of stage `it` have landed
         __syncthreads();                    // ... and everyone's; the other buffer is free
-        if (it + 1 < n_tiles) issue_tile_loads<D, NW, BN>(ks, tp, it + 1, wave, lane, Ks1, Vs1);
-        tp = load_tile_pages<BN>(ks, it + 2);
-        consume(it, Ks0, Vs0);
-        if (it + 1 >= n_tiles) break;
-        __builtin_amdgcn_s_waitcnt(0);
+        if (it + 1 < n_stages) {
+            const uint32_t nb = smem_lds + (cur ^ 1) * 2 * STAGE_BYTES;
+            issue_stage_loads<D, KS>(ks, lo, page, it + 1, wave, lane, new_row_bytes, nb, nb + STAGE_BYTES);
+        }
+        page = load_stage_page<KS>(ks, it + 2, wave);
+        stage(it, smem + cur * 2 * STAGE_U4, smem + cur * 2 * STAGE_U4 + STAGE_U4);
+    }
+
+    // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes
+    float ltot = half_swap_sum(lsum);
+    if constexpr (KS == 2) {
+        __syncthreads();                    // all stage buffers are dead now
+        float *part = reinterpret_cast<float *>(smem) + slot * (DBLK * 16 * 64);
+        if (kq == 1) {
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) part[(db * 16 + v) * 64 + lane] = o[db][v];
+            if (half == 0) { Mstat[slot][0][l32] = m; Mstat[slot][1][l32] = ltot; }
+        }
         __syncthreads();
-        if (it + 2 < n_tiles) issue_tile_loads<D, NW, BN>(ks, tp, it + 2, wave, lane, Ks0, Vs0);
-        tp = load_tile_pages<BN>(ks, it + 3);
-        consume(it + 1, Ks1, Vs1);
+        if (kq == 1) return;
+        const float m1 = Mstat[slot][0][l32], l1 = Mstat[slot][1][l32];
+        const float mstar = fmaxf(m, m1);
+        const float w0 = __builtin_amdgcn_exp2f(m - mstar), w1 = __builtin_amdgcn_exp2f(m1 - mstar);
+        ltot = ltot * w0 + l1 * w1;
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] = o[db][v] * w0 + part[(db * 16 + v) * 64 + lane] * w1;
     }
 
     // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
     if (!row_ok) return;
-    const float inv = __builtin_amdgcn_rcpf(half_swap_sum(lsum));
+    const float inv = __builtin_amdgcn_rcpf(ltot);
     uint16_t *orow = p.out + ((size_t)(ks.row_base + t) * p.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
@@ -342,22 +390,21 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(AttnParams p)
         }
 }
 
-template <int D, int NW, int BN>
+template <int D, int KS>
 hipError_t launch(const AttnParams &p, hipStream_t stream)
 {
     const int groups = p.Hq / p.hpw;
     const int nwg = p.tiles * groups;
     const int grid = (nwg + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), dim3(grid), dim3(NW * 64), 0, stream, p);
+    hipLaunchKernelGGL((attn_tile_kernel<D, KS>), dim3(grid), dim3(kSlots * KS * 64), 0, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, hipStream_t stream)
+hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream)
 {
-    const int nw = p.hpw * p.rb;
     if (h->cfg.head_dim == 128)
-        return nw == 4 ? launch<128, 4, 64>(p, stream) : launch<128, 2, 32>(p, stream);
-    return nw == 4 ? launch<64, 4, 64>(p, stream) : launch<64, 2, 32>(p, stream);
+        return key_parts == 2 ? launch<128, 2>(p, stream) : launch<128, 1>(p, stream);
+    return key_parts == 2 ? launch<64, 2>(p, stream) : launch<64, 1>(p, stream);
 }

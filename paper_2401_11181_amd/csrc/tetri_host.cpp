@@ -26,14 +26,14 @@ tetri_status fail(tetri_ctx *h, tetri_status st, const char *fmt, ...)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Query-head grouping of a workgroup of nw (4 or 2) wavefronts: its wavefronts are
+// Query-head grouping of a workgroup: its 4 row/head slots are
 // (hpw heads that share a kv head) x (rb blocks of 32 rows).
-void wave_grouping(int g, int nw, int *hpw, int *rb)
+void wave_grouping(int g, int *hpw, int *rb)
 {
-    if (g % nw == 0) *hpw = nw;
-    else if (g % 2 == 0 && nw % 2 == 0) *hpw = 2;
+    if (g % 4 == 0) *hpw = 4;
+    else if (g % 2 == 0) *hpw = 2;
     else *hpw = 1;
-    *rb = nw / *hpw;
+    *rb = 4 / *hpw;
 }
 
 // Upper bound of the number of row tiles of a chunk: each of the S segments and the padding
@@ -86,7 +86,7 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
 {
     if (!ctx || !key) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: null argument");
     if (std::strcmp(key, "attn_variant") == 0) {
-        if (value < 0 || value > 2) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
+        if (value < 0 || value > 3) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
         ctx->attn_variant = value;
         return TETRI_OK;
     }
@@ -220,21 +220,22 @@ tetri_status tetri_chunk_prefill_attn(tetri_ctx *h, const void *q, const void *k
     p.out = static_cast<uint16_t *>(out);
     p.S = num_segs; p.C = h->cfg.chunk_size; p.Hq = h->cfg.num_q_heads; p.Hkv = h->cfg.num_kv_heads;
     p.g = p.Hq / p.Hkv;
-    // 4-wave workgroups share each K/V tile among 128 rows; when that leaves the 256 CUs with
-    // fewer than two workgroups each, 2-wave workgroups (twice as many, half the LDS) fill better.
-    int nw = 4;
-    wave_grouping(p.g, 4, &p.hpw, &p.rb);
+    wave_grouping(p.g, &p.hpw, &p.rb);
     p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
-    const bool small_grid = (long long)p.tiles * (p.Hq / p.hpw) < 512;
-    if (h->attn_variant == 2 || (h->attn_variant == 0 && small_grid)) nw = 2;
-    if (nw == 2) {
-        wave_grouping(p.g, 2, &p.hpw, &p.rb);
-        p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
-    }
     p.max_blocks = h->cfg.max_blocks_per_seq;
-    p.c = std::fabs(scale) * 1.4426950408889634f;
+    // scale == 0 is run as a tiny positive scale: every finite score then maps to weight 1 exactly,
+    // while masked scores (-inf) still map to weight 0
+    p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     p.neg = scale < 0.f;
-    hipError_t e = tetri_launch_attn(h, p, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (h->attn_variant == 3) {
+        // key-split kernel: one workgroup per (head, 32-row block)
+        p.hpw = 1; p.rb = 1;
+        p.tiles = tile_bound(p.C, p.S, 32);
+        e = tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream));
+    } else {
+        e = tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));
+    }
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "tetri_chunk_prefill_attn: launch failed: %s", hipGetErrorString(e));
     return TETRI_OK;
 }

@@ -9,7 +9,7 @@
 struct tetri_ctx {
     tetri_config cfg;
     std::string err;
-    int attn_variant = 0;   // 0 = choose by grid size, 1 = 4-wave workgroups, 2 = 2-wave workgroups
+    int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts, 3 = key-split kernel
 };
 
 // Launch parameters of the attention kernels (passed by value).
@@ -33,5 +33,6 @@ struct AppendParams {
     int32_t S, Hkv, D, max_blocks;
 };
 
-hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
+hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
+hipError_t tetri_launch_attn_split(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
 hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

@@ -18,10 +18,11 @@ def workload_tensors(w):
     return qs, ks, vs, synth.place_pages(w)
 
 
-def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False):
+def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False, variant=0):
     """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
     sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                           w.num_pages, tables, device=DEV, page_size=w.page_size)
+    sess.handle.tetri_set_option("attn_variant", variant)
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
     dq = [t.to(DEV) for t in qs]
     dk = [t.to(DEV) for t in ks]

@@ -13,6 +13,15 @@ import gpu_common as gc
 
 pytestmark = pytest.mark.gpu
 
+# attention kernel variants: 0 = library's choice, 1 / 2 = shared-tile kernel with 4 / 2 wavefronts,
+# 3 = key-split kernel.  Every variant must meet the same bar.
+VARIANTS = [0, 1, 2, 3]
+
+
+@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "split"])
+def variant(request):
+    return request.param
+
 
 def run_case(oracle, w, **kw):
     qs, ks, vs, tables = gc.workload_tensors(w)
@@ -27,9 +36,9 @@ def run_case(oracle, w, **kw):
     return stats
 
 
-def test_tiny_config(oracle):
+def test_tiny_config(oracle, variant):
     """Config 'tiny' rounded to bf16: 256 tokens, 4 chunks of 64, 4 heads x 64."""
-    print(run_case(oracle, synth.workload("tiny")))
+    print(run_case(oracle, synth.workload("tiny"), variant=variant))
 
 
 CASES = {
@@ -49,49 +58,49 @@ CASES = {
 
 
 @pytest.mark.parametrize("name", sorted(CASES))
-def test_shapes(oracle, name):
+def test_shapes(oracle, name, variant):
     lens, chunk, hq, hkv, d = CASES[name]
     w = synth.small(name, lens, chunk, hq, hkv, d, seed=100 + sorted(CASES).index(name))
-    print(name, run_case(oracle, w))
+    print(name, run_case(oracle, w, variant=variant))
 
 
-def test_append_before_attention_gives_same_result(oracle):
+def test_append_before_attention_gives_same_result(oracle, variant):
     w = synth.small("order", [90, 75, 20], 64, 4, 2, 128, seed=130)
     qs, ks, vs, tables = gc.workload_tensors(w)
-    a, pool_a, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
-    b, pool_b, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, append_first=True)
+    a, pool_a, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=variant)
+    b, pool_b, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, append_first=True, variant=variant)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
     assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
 
 
 @pytest.mark.parametrize("fill", [3.0e4, float("nan")])
-def test_padding_rows_are_inert(oracle, fill):
+def test_padding_rows_are_inert(oracle, fill, variant):
     w = synth.small("pad", [100, 37], 64, 2, 2, 128, seed=131)
     qs, ks, vs, tables = gc.workload_tensors(w)
-    ref, pool_ref, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
-    out, pool, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, pad_fill=fill)
+    ref, pool_ref, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=variant)
+    out, pool, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, pad_fill=fill, variant=variant)
     for x, y in zip(ref, out):
         assert torch.equal(x, y)
     assert torch.equal(pool_ref.view(torch.int16), pool.view(torch.int16))
 
 
-def test_deterministic(oracle):
+def test_deterministic(oracle, variant):
     w = synth.small("det", [200, 120], 128, 4, 4, 128, seed=132)
     qs, ks, vs, tables = gc.workload_tensors(w)
-    a, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
-    b, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
+    a, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=variant)
+    b, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=variant)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
 
 
 @pytest.mark.parametrize("scale", [0.0, -0.2, 1.7])
-def test_scales(oracle, scale):
+def test_scales(oracle, scale, variant):
     w = synth.small("scale", [90, 45], 64, 2, 2, 64, seed=133, scale=scale)
-    print(scale, run_case(oracle, w))
+    print(scale, run_case(oracle, w, variant=variant))
 
 
-def test_spiky_scores(oracle):
+def test_spiky_scores(oracle, variant):
     """One key scores about +20 above the rest for every query: exercises the running-max rescale."""
     w = synth.small("spiky", [300], 128, 2, 2, 128, seed=134)
     qs, ks, vs, tables = gc.workload_tensors(w)
@@ -101,16 +110,16 @@ def test_spiky_scores(oracle):
     k[150, :, 0] = 16.0
     q[:, :, 0] = 20.0 * (128 ** 0.5) / 16.0
     qs, ks = [q.to(torch.bfloat16)], [k.to(torch.bfloat16)]
-    outs, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
+    outs, _, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=variant)
     ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
     print(gc.compare(outs, ref, label="spiky"))
 
 
-def test_opt13b_config_full(oracle):
+def test_opt13b_config_full(oracle, variant):
     """The benchmark configuration (40 x 128, ChunkSize 512, 2048-token prompt), every output element."""
     w = synth.workload("opt13b")
-    stats = run_case(oracle, w)
+    stats = run_case(oracle, w, variant=variant)
     print(stats)
     sharp = synth.sharp(w)
     sharp.seed = 2002
-    print(run_case(oracle, sharp))
+    print(run_case(oracle, sharp, variant=variant))

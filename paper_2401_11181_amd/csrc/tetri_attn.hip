@@ -245,110 +245,146 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         }
     };
 
-    // One 32-key block for this wavefront: keys key0 .. key0+31 at rows row0 .. row0+31 of the stage
-    // buffers; its K fragments are already in kf.  If next_row0 >= 0 the K fragments of the block at
-    // that row are fetched into kf while the PV product runs.  The running max / sum / O are
-    // updated per block (online softmax); the max is only raised when a row's block maximum
-    // exceeds it by more than 2^8, so weights stay below 2^8 and O is rescaled rarely.
-    auto consume = [&](bool need_mask, int bound, int key0, int row0, int next_row0, bf16x8 (&kf)[KSTEPS],
-                       const uint4 *Kt, const uint4 *Vt) {
-        // ---- S^T = K Q^T for 32 keys x 32 queries
-        f32x16 sacc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st)
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qf[st], sacc, 0, 0, 0);
-        // V fragments of this block travel from LDS while the scores are computed and exponentiated
-        s16x8 vf[2 * DBLK];
-        load_v(vf, row0, Vt);
-        // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
-        // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
-        if (need_mask) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
-                if (key > bound) sacc[v] = -INFINITY;
-            }
-        }
-        // ---- online softmax (per query = per lane pair)
-        float mx = sacc[0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
-        mx = half_swap_max(mx) * c;
-        if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
-            const float m_new = fmaxf(m, mx);
-            float alpha = __builtin_amdgcn_exp2f(m - m_new);
-            // the wait state a transcendental result needs before a VALU use; the compiler does not
-            // insert it in front of inline assembly
-            asm volatile("s_nop 1" : "+v"(alpha));
-            m = m_new;
-            lsum *= alpha;
-            // in place, so that the accumulators keep their registers on both paths
-#pragma unroll
-            for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(o[i][v]) : "v"(alpha));
-        }
-        bf16x8 pf[2];
-        bf16x2 ones;
-        ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-            bf16x2 pp;
-            pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], c, -m));
-            pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v + 1], c, -m));
-            // the row sum is taken over the rounded weights, the ones the PV product uses
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
-            pf[v / 8][v % 8] = pp[0];
-            pf[v / 8][v % 8 + 1] = pp[1];
-        }
-        // K fragments of the next block travel while the PV product runs
-        if (next_row0 >= 0) load_k(kf, next_row0, Kt);
-        // ---- O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
-    };
-
-    auto stage = [&](int it, const uint4 *Kt, const uint4 *Vt) {
-        if (!wave_has_rows) return;
+    // Number of 32-key blocks of stage `it` this wavefront works on (a prefix of its 64-key part):
+    // those inside the key range and not entirely past the wavefront's rows.
+    auto stage_blocks = [&](int it) -> int {
+        if (!wave_has_rows) return 0;
         const bool is_ctx = it < ks.n_ctx_tiles;
-        const int part0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW;   // first key of this wavefront's part
-        // active blocks (a prefix of the part): inside the key range and not past this wavefront's rows
+        const int part0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW;
         int nblk = 0;
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
             const int key0 = part0 + kb * 32;
             if (is_ctx ? key0 < L : (key0 < ks.n_new && key0 <= tw0 + 31)) nblk = kb + 1;
         }
-        if (nblk == 0) return;
-        const int bound = is_ctx ? L - 1 : t;          // last visible key index of this phase
-        bf16x8 kf[KSTEPS];
-        load_k(kf, kq * kBNW, Kt);
-#pragma unroll 1
-        for (int kb = 0; kb < nblk; ++kb) {
-            const int key0 = part0 + kb * 32;
-            const int row0 = kq * kBNW + kb * 32;
-            const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
-            consume(need_mask, bound, key0, row0, (kb + 1 < nblk) ? row0 + 32 : -1, kf, Kt, Vt);
-        }
+        return nblk;
     };
-
-    // ---- main loop.  `page` always belongs to the stage whose loads are issued next; it is
-    // fetched one stage ahead.
-    for (int it = 0; it < n_stages; ++it) {
-        const int cur = it & 1;
-        wait_vm<0>();                       // this wavefront's loads of stage `it` have landed
-        __syncthreads();                    // ... and everyone's; the other buffer is free
+    // Make stage `it` the current one: its loads have landed for every wavefront, nobody reads the
+    // other buffer any more, so the loads of stage it+1 can go there.  `page` always belongs to
+    // the stage whose loads are issued next; it is fetched one stage ahead.
+    auto enter_stage = [&](int it) {
+        wait_vm<0>();
+        __syncthreads();
         if (it + 1 < n_stages) {
-            const uint32_t nb = smem_lds + (cur ^ 1) * 2 * STAGE_BYTES;
+            const uint32_t nb = smem_lds + ((it + 1) & 1) * 2 * STAGE_BYTES;
             issue_stage_loads<D, KS>(ks, lo, page, it + 1, wave, lane, new_row_bytes, nb, nb + STAGE_BYTES);
         }
         page = load_stage_page<KS>(ks, it + 2, wave);
-        stage(it, smem + cur * 2 * STAGE_U4, smem + cur * 2 * STAGE_U4 + STAGE_U4);
+    };
+    auto qk = [&](const bf16x8 (&kf)[KSTEPS]) -> f32x16 {
+        f32x16 sacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st)
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qf[st], sacc, 0, 0, 0);
+        return sacc;
+    };
+
+    // ---- main loop over this wavefront's blocks, software pipelined: while the softmax of block b
+    // runs on the VALU, the matrix cores compute the scores of block b+1; then O += V_b P_b.
+    // Every wavefront enters every stage exactly once (one barrier each), whether or not it has
+    // blocks there.
+    int it = 0;
+    enter_stage(0);
+    int nblk = stage_blocks(0);
+    while (nblk == 0 && ++it < n_stages) {
+        enter_stage(it);
+        nblk = stage_blocks(it);
+    }
+    if (it < n_stages) {
+        int kb = 0;
+        bf16x8 kf[KSTEPS];
+        load_k(kf, kq * kBNW, smem + (it & 1) * 2 * STAGE_U4);
+        f32x16 s_cur = qk(kf);
+        for (;;) {
+            const bool is_ctx = it < ks.n_ctx_tiles;
+            const int key0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
+            const int row0 = kq * kBNW + kb * 32;
+            const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
+            const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
+            // V fragments of this block: in registers before the stage may be left
+            s16x8 vf[2 * DBLK];
+            load_v(vf, row0, smem + (it & 1) * 2 * STAGE_U4 + STAGE_U4);
+            // ---- the block after this one
+            bool have_next = true;
+            if (kb + 1 < nblk) {
+                ++kb;
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS
+                kb = 0;
+                nblk = 0;
+                while (nblk == 0 && ++it < n_stages) {
+                    enter_stage(it);
+                    nblk = stage_blocks(it);
+                }
+                have_next = it < n_stages;
+            }
+            if (have_next) load_k(kf, kq * kBNW + kb * 32, smem + (it & 1) * 2 * STAGE_U4);
+            // ---- this block's scores: mask, row max.  Accumulator element v is key
+            // key0 + (v/4)*8 + 4*half + v%4; keys past `bound` (the end of the cached context, or the
+            // query's own position) get weight exp2(-inf) = 0.
+            if (need_mask) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
+                    if (key > bound) s_cur[v] = -INFINITY;
+                }
+            }
+            float mx = s_cur[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
+            mx = half_swap_max(mx) * c;
+            // The running max is only raised when a row's block maximum exceeds it by more than 2^8, so
+            // weights stay below 2^8 and O is rescaled rarely.
+            if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
+                const float m_new = fmaxf(m, mx);
+                float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                // the wait state a transcendental result needs before a VALU use; the compiler does not
+                // insert it in front of inline assembly
+                asm volatile("s_nop 1" : "+v"(alpha));
+                m = m_new;
+                lsum *= alpha;
+                // in place, so that the accumulators keep their registers on both paths
+#pragma unroll
+                for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(o[i][v]) : "v"(alpha));
+            }
+            // ---- one straight-line region: the scores of the next block (discarded after the last
+            // one) on the matrix cores, interleaved with exponentiating and rounding this block's
+            // weights on the VALU; then O^T += V^T P^T.
+            __builtin_amdgcn_sched_barrier(0);
+            const f32x16 s_next = qk(kf);
+            bf16x8 pf[2];
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                bf16x2 pp;
+                pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[v], c, -m));
+                pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[v + 1], c, -m));
+                // the row sum is taken over the rounded weights, the ones the PV product uses
+                lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
+                pf[v / 8][v % 8] = pp[0];
+                pf[v / 8][v % 8 + 1] = pp[1];
+            }
+            // Step j contracts the 16 keys held in accumulator elements 8j..8j+7
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
+            // wanted order: one MFMA of the score chain, then 6 VALU operations of the softmax, 8 times
+#pragma unroll
+            for (int g = 0; g < KSTEPS; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (!have_next) break;
+            s_cur = s_next;
+        }
     }
 
     // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes

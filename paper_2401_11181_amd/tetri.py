@@ -11,7 +11,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtetri.so")
+# TETRI_LIB selects another build of the same library (used when comparing kernel builds)
+LIB_PATH = os.environ.get("TETRI_LIB") or os.path.join(_HERE, "libtetri.so")
 
 TETRI_OK = 0
 TETRI_ERR_INVALID_ARG = -1

@@ -133,6 +133,25 @@ TETRI_API tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t n
                                   int32_t *cu_out, int32_t *ctx_out, int32_t *block_table_out);
 
 /*
+ * Packing and metadata of a whole scheduled batch in one host call: tetri_pack_chunks followed by
+ * tetri_chunk_metadata for every chunk, written back to back into one caller buffer that can be
+ * uploaded with a single copy.
+ *   meta_out [meta_capacity] host, out: for chunk c, cu at layout_out[4c+0], ctx_lens at
+ *            layout_out[4c+1], block_table at layout_out[4c+2] (offsets in int32 units, each a
+ *            multiple of 4 so that every array stays 16-byte aligned); layout_out[4c+3] = num_segs
+ *   layout_out [4 * chunk_capacity] host, out
+ * Query mode: meta_out == NULL and layout_out == NULL: nothing is written except *meta_len_out.
+ * *meta_len_out (may be NULL) receives the number of int32 the metadata needs.
+ * Returns the number of chunks or a negative tetri_status (as tetri_pack_chunks; TETRI_ERR_NOMEM if
+ * a capacity is too small).
+ */
+TETRI_API int32_t tetri_plan_metadata(const int32_t *prompt_lens, int32_t n_prompts,
+                                      const int32_t *order, int32_t n_order, int32_t chunk_size,
+                                      const int32_t *req_block_tables, int32_t max_blocks_per_seq,
+                                      int32_t *meta_out, int64_t meta_capacity,
+                                      int32_t *layout_out, int32_t chunk_capacity, int64_t *meta_len_out);
+
+/*
  * KV append (Sec. 2.1: prefill generates the KV cache; Sec. 3.4: kept in pages).
  * For every segment s, local token t < n_s and kv head: copy k_new / v_new[cu[s] + t][head][:]
  * bit for bit into slot (ctx_lens[s] + t) % page_size of page

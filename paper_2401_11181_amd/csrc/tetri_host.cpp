@@ -168,6 +168,48 @@ tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t num_segs, c
     return TETRI_OK;
 }
 
+int32_t tetri_plan_metadata(const int32_t *prompt_lens, int32_t n_prompts, const int32_t *order, int32_t n_order,
+                            int32_t chunk_size, const int32_t *req_block_tables, int32_t max_blocks,
+                            int32_t *meta_out, int64_t meta_capacity, int32_t *layout_out, int32_t chunk_capacity,
+                            int64_t *meta_len_out)
+{
+    if (!req_block_tables || max_blocks < 1)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_plan_metadata: null block tables or max_blocks_per_seq < 1");
+    const bool query = (meta_out == nullptr && layout_out == nullptr);
+    if (!query && (!meta_out || !layout_out))
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_plan_metadata: meta_out and layout_out must both be given or both be null");
+    int32_t n_segs = 0;
+    const int32_t n_chunks = tetri_pack_chunks(prompt_lens, n_prompts, order, n_order, chunk_size, nullptr, 0, nullptr, 0, &n_segs);
+    if (n_chunks < 0) return n_chunks;
+    thread_local std::vector<tetri_segment> segs;
+    thread_local std::vector<int32_t> offs;
+    segs.resize((size_t)n_segs + 1);
+    offs.resize((size_t)n_chunks + 1);
+    int32_t rc = tetri_pack_chunks(prompt_lens, n_prompts, order, n_order, chunk_size, segs.data(), n_segs, offs.data(), n_chunks, nullptr);
+    if (rc < 0) return rc;
+    if (!query && n_chunks > chunk_capacity)
+        return fail(nullptr, TETRI_ERR_NOMEM, "tetri_plan_metadata: chunk_capacity=%d too small for %d chunks", chunk_capacity, n_chunks);
+    auto up4 = [](int64_t x) { return (x + 3) / 4 * 4; };
+    int64_t at = 0;
+    for (int32_t c = 0; c < n_chunks; ++c) {
+        const int32_t S = offs[c + 1] - offs[c];
+        const int64_t o_cu = at, o_ctx = o_cu + up4(S + 1), o_bt = o_ctx + up4(S);
+        at = o_bt + up4((int64_t)S * max_blocks);
+        if (query) continue;
+        if (at > meta_capacity || at > INT32_MAX)
+            return fail(nullptr, TETRI_ERR_NOMEM, "tetri_plan_metadata: meta_capacity=%lld too small", (long long)meta_capacity);
+        layout_out[4 * c + 0] = (int32_t)o_cu;
+        layout_out[4 * c + 1] = (int32_t)o_ctx;
+        layout_out[4 * c + 2] = (int32_t)o_bt;
+        layout_out[4 * c + 3] = S;
+        tetri_status st = tetri_chunk_metadata(segs.data() + offs[c], S, req_block_tables, n_prompts, max_blocks,
+                                               meta_out + o_cu, meta_out + o_ctx, meta_out + o_bt);
+        if (st != TETRI_OK) return st;
+    }
+    if (meta_len_out) *meta_len_out = at;
+    return n_chunks;
+}
+
 static tetri_status check_common(tetri_ctx *h, const char *fn, const void *const *ptrs, const char *const *names, int n,
                                  int32_t num_segs)
 {

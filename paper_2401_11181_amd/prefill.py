@@ -95,16 +95,16 @@ class ChunkedPrefill:
 class PrefillPipeline:
     """The whole hot path of one scheduled batch as a repeatable step, for measurement.
 
-    step() = pack the batch into chunks on the host (tetri_pack_chunks), build every chunk's
-    metadata (tetri_chunk_metadata) into pinned host memory, one asynchronous upload, then for
-    every chunk in order one attention launch and one append launch (Sec. 3.3.3: one chunk at a
-    time; the progress variable of each request is the `start` field of its next segment).
+    step() = pack the batch into chunks and build every chunk's metadata on the host
+    (tetri_plan_metadata, one C call) into pinned memory, one asynchronous upload, then for every
+    chunk in order one attention launch and one append launch (Sec. 3.3.3: one chunk at a time; the
+    progress variable of each request is the `start` field of its next segment).
     Inputs (per-chunk q, k_new, v_new) and the page pool are resident in HBM before a step.
-    With use_graph the upload and the launches of a step are replayed from a HIP graph; packing
-    and metadata still run on the host every step.
+    With use_graph the launches of a step are replayed from a HIP graph; packing, metadata and the
+    upload still run every step.
     """
 
-    RING = 4    # staging buffers in flight
+    RING = 4    # pinned staging buffers in flight
 
     def __init__(self, prompt_lens, order, chunk_size, num_q_heads, num_kv_heads, head_dim, num_pages,
                  req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False):
@@ -117,103 +117,88 @@ class PrefillPipeline:
         self.req_bt = np.zeros((len(req_block_tables), self.max_blocks), dtype=np.int32)
         for r, t in enumerate(req_block_tables):
             self.req_bt[r, :len(t)] = t
-        segs, offsets = tetri.tetri_pack_chunks(self.lens, self.order, chunk_size)
-        self.n_chunks = len(offsets) - 1
-        self.seg_counts = [int(offsets[c + 1] - offsets[c]) for c in range(self.n_chunks)]
-        self.max_segs = max([1] + self.seg_counts)
-        self.segs_buf = np.zeros((len(segs) + 1, 3), dtype=np.int32)
-        self.offs_buf = np.zeros(self.n_chunks + 1, dtype=np.int32)
-        self.plan_segs = segs.copy()
-        self.plan_offsets = offsets.copy()
-        self.handle = tetri.Tetri(num_q_heads, num_kv_heads, head_dim, chunk_size, num_pages, self.max_blocks,
-                                  self.max_segs, page_size=page_size)
-        # fixed layout of the metadata block: per chunk cu | ctx | block_table, each 16-byte aligned
-        def up4(x):
-            return (x + 3) // 4 * 4
-        self.layout, at = [], 0
-        for c in range(self.n_chunks):
-            S = self.seg_counts[c]
-            o_cu, at = at, at + up4(S + 1)
-            o_ctx, at = at, at + up4(S)
-            o_bt, at = at, at + up4(S * self.max_blocks)
-            self.layout.append((o_cu, o_ctx, o_bt, S))
-        self.meta_len = max(at, 4)
+        self.plan_segs, self.plan_offsets = tetri.tetri_pack_chunks(self.lens, self.order, chunk_size)
+        self.n_chunks, self.meta_len = tetri.tetri_plan_metadata(self.lens, self.order, chunk_size, self.req_bt)
+        self.meta_len = max(int(self.meta_len), 4)
         self.stage = [torch.zeros(self.meta_len, dtype=torch.int32, pin_memory=True) for _ in range(self.RING)]
-        self.stage_np = [t.numpy() for t in self.stage]
+        self.layout_np = np.zeros((max(self.n_chunks, 1), 4), dtype=np.int32)
         self.meta_dev = torch.zeros(self.meta_len, dtype=torch.int32, device=self.device)
-        self.events = [None] * self.RING
-        self.graphs = [None] * self.RING
+        self.host_plan(0)
+        self.layout = [tuple(int(x) for x in row) for row in self.layout_np[:self.n_chunks]]
+        max_segs = max([1] + [l[3] for l in self.layout])
+        self.handle = tetri.Tetri(num_q_heads, num_kv_heads, head_dim, chunk_size, num_pages, self.max_blocks,
+                                  max_segs, page_size=page_size)
+        self.events = [torch.cuda.Event() for _ in range(self.RING)]
+        self.used = [False] * self.RING
+        self.graph = None
         self.use_graph = use_graph
         self.turn = 0
-        self._lib = tetri.lib()
-        self._ptrs = None
 
     # --- inputs -------------------------------------------------------------------------------
     def bind(self, q_chunks, k_chunks, v_chunks, kv_pages, out_chunks):
         """Device tensors: q/out [n_chunks,C,Hq,D], k/v [n_chunks,C,Hkv,D], the page pool."""
         self.q, self.k, self.v, self.pool, self.out = q_chunks, k_chunks, v_chunks, kv_pages, out_chunks
-        self.graphs = [None] * self.RING
+        self.graph = None
+        self._bind_args()
 
     # --- host part of a step --------------------------------------------------------------------
     def host_plan(self, slot):
-        """a1: pack; then every chunk's cu / ctx / block table into staging buffer `slot`."""
-        import ctypes
-        L = self._lib
-        n_segs = ctypes.c_int32(0)
-        n_order = len(self.lens) if self.order is None else len(self.order)
-        n = L.tetri_pack_chunks(tetri._ptr(self.lens), len(self.lens), tetri._ptr(self.order), n_order, self.C,
-                                tetri._ptr(self.segs_buf), len(self.segs_buf), tetri._ptr(self.offs_buf),
-                                self.n_chunks, ctypes.byref(n_segs))
+        """a1: pack, and every chunk's cu / ctx / block table into staging buffer `slot`."""
+        n = tetri.tetri_plan_metadata(self.lens, self.order, self.C, self.req_bt, self.stage[slot], self.layout_np)
         if n != self.n_chunks:
-            raise tetri.TetriError(n, tetri.tetri_last_error())
-        base = self.stage[slot].data_ptr()
-        segs_ptr = self.segs_buf.ctypes.data
-        rbt = tetri._ptr(self.req_bt)
-        for c in range(self.n_chunks):
-            o_cu, o_ctx, o_bt, S = self.layout[c]
-            rc = L.tetri_chunk_metadata(ctypes.c_void_p(segs_ptr + 12 * int(self.offs_buf[c])), S, rbt,
-                                        self.req_bt.shape[0], self.max_blocks,
-                                        ctypes.c_void_p(base + 4 * o_cu), ctypes.c_void_p(base + 4 * o_ctx),
-                                        ctypes.c_void_p(base + 4 * o_bt))
-            if rc != tetri.TETRI_OK:
-                raise tetri.TetriError(rc, tetri.tetri_last_error())
+            raise RuntimeError("plan changed between steps")
 
     # --- device part of a step ------------------------------------------------------------------
-    def _launch_all(self, slot, timing=None):
-        self.meta_dev.copy_(self.stage[slot], non_blocking=True)
+    def _bind_args(self):
+        """Marshal the arguments of every launch once (ctypes objects), so that a launch is one foreign call."""
+        import ctypes
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
         base = self.meta_dev.data_ptr()
-        h = self.handle
+        self._attn_args, self._app_args = [], []
         for c in range(self.n_chunks):
             o_cu, o_ctx, o_bt, S = self.layout[c]
-            cu, ctx, bt = base + 4 * o_cu, base + 4 * o_ctx, base + 4 * o_bt
-            if timing is not None:
-                timing[c][0].record()
-            h.tetri_chunk_prefill_attn(self.q[c], self.k[c], self.v[c], self.pool, bt, cu, ctx, S, self.scale,
-                                       self.out[c])
-            if timing is not None:
-                timing[c][1].record()
-            h.tetri_kv_append(self.k[c], self.v[c], self.pool, bt, cu, ctx, S)
-            if timing is not None:
-                timing[c][2].record()
+            q, k, v, o = (vp(t[c].data_ptr()) for t in (self.q, self.k, self.v, self.out))
+            pool = vp(self.pool.data_ptr())
+            bt, cu, ctx = vp(base + 4 * o_bt), vp(base + 4 * o_cu), vp(base + 4 * o_ctx)
+            self._attn_args.append((self.handle.h, q, k, v, pool, bt, cu, ctx, i32(S), f32(self.scale), o))
+            self._app_args.append((self.handle.h, k, v, pool, bt, cu, ctx, i32(S)))
+        self._lib = tetri.lib()
 
-    def step(self, timing=None):
+    def launch_attn(self, c, stream=None):
+        """One attention launch of chunk c with the metadata currently on the device."""
+        rc = self._lib.tetri_chunk_prefill_attn(*self._attn_args[c], stream or tetri._stream(None))
+        if rc != tetri.TETRI_OK:
+            raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
+
+    def launch_append(self, c, stream=None):
+        rc = self._lib.tetri_kv_append(*self._app_args[c], stream or tetri._stream(None))
+        if rc != tetri.TETRI_OK:
+            raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
+
+    def _launch_all(self):
+        stream = tetri._stream(None)                # the current stream, looked up once per step
+        for c in range(self.n_chunks):
+            self.launch_attn(c, stream)
+            self.launch_append(c, stream)
+
+    def step(self):
         slot = self.turn % self.RING
         self.turn += 1
-        if self.events[slot] is not None:
+        if self.used[slot]:
             self.events[slot].synchronize()         # the upload that last used this buffer is done
         self.host_plan(slot)
-        if self.use_graph and timing is None:
-            if self.graphs[slot] is None:
+        self.meta_dev.copy_(self.stage[slot], non_blocking=True)
+        self.events[slot].record()
+        self.used[slot] = True
+        if self.use_graph:
+            if self.graph is None:                  # one graph: the launches read meta_dev, whose address is fixed
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g):
-                    self._launch_all(slot)
-                self.graphs[slot] = g
-            self.graphs[slot].replay()
+                    self._launch_all()
+                self.graph = g
+            self.graph.replay()
         else:
-            self._launch_all(slot, timing)
-        ev = torch.cuda.Event()
-        ev.record()
-        self.events[slot] = ev
+            self._launch_all()
 
     # --- bookkeeping ----------------------------------------------------------------------------
     def chunk_segments(self, c):

@@ -62,6 +62,9 @@ def lib():
         L.tetri_pack_chunks.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp, i32, ctypes.POINTER(i32)]
         L.tetri_chunk_metadata.restype = i32
         L.tetri_chunk_metadata.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
+        L.tetri_plan_metadata.restype = i32
+        L.tetri_plan_metadata.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp, ctypes.c_int64, vp, i32,
+                                          ctypes.POINTER(ctypes.c_int64)]
         L.tetri_kv_append.restype = i32
         L.tetri_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.tetri_chunk_prefill_attn.restype = i32
@@ -134,6 +137,29 @@ def tetri_chunk_metadata(segs, req_block_tables):
     if rc != TETRI_OK:
         raise TetriError(rc, tetri_last_error())
     return cu, ctx, bt
+
+
+def tetri_plan_metadata(prompt_lens, order, chunk_size, req_block_tables, meta_out=None, layout_out=None):
+    """tetri_plan_metadata (host).  Without buffers: returns (n_chunks, meta_len).  With meta_out (int32
+    array / pinned tensor) and layout_out (int32 [n_chunks,4]): fills them and returns n_chunks."""
+    L = lib()
+    lens = np.ascontiguousarray(prompt_lens, dtype=np.int32)
+    ordr = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+    rbt = np.ascontiguousarray(req_block_tables, dtype=np.int32)
+    n_order = len(lens) if ordr is None else len(ordr)
+    meta_len = ctypes.c_int64(0)
+    if meta_out is None:
+        n = L.tetri_plan_metadata(_ptr(lens), len(lens), _ptr(ordr), n_order, int(chunk_size), _ptr(rbt),
+                                  rbt.shape[1], None, 0, None, 0, ctypes.byref(meta_len))
+        if n < 0:
+            raise TetriError(n, tetri_last_error())
+        return n, meta_len.value
+    n = L.tetri_plan_metadata(_ptr(lens), len(lens), _ptr(ordr), n_order, int(chunk_size), _ptr(rbt),
+                              rbt.shape[1], _ptr(meta_out), meta_out.numel() if isinstance(meta_out, torch.Tensor)
+                              else meta_out.size, _ptr(layout_out), layout_out.shape[0], ctypes.byref(meta_len))
+    if n < 0:
+        raise TetriError(n, tetri_last_error())
+    return n
 
 
 class Tetri:

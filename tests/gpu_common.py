@@ -91,3 +91,28 @@ def compare(gpu_outs, ref_outs, max_abs=2e-2, mean_abs=2e-3, rel_l2=1e-2, label=
     stats = dict(max_abs=err.max(), mean_abs=err.mean(), rel_l2=rel)
     assert err.max() <= max_abs and err.mean() <= mean_abs and rel <= rel_l2, (label, stats)
     return stats
+
+
+def oracle_chunk_samples(oracle, w, segs, q_chunk, k_chunk, v_chunk, ks, vs, rows, heads):
+    """Oracle outputs of sampled (row, head) pairs of one chunk of a large workload.
+
+    The cached context of the chunk's segments is rebuilt in a compact float32 pool with the
+    oracle's own append (physical placement does not matter: pinned by the paging invariant), so
+    that the full-size pool never has to exist on the host.  q/k/v_chunk: float32 [C,H,D] rows of the
+    chunk; ks/vs: per-request bf16 tensors (only the chunk's requests are touched).
+    """
+    P, Hkv, D = w.page_size, w.num_kv_heads, w.head_dim
+    pages_per_seg = [-(-(start + n) // P) for _req, start, n in segs]
+    pool = np.zeros((max(1, sum(pages_per_seg)), 2, Hkv, P, D), dtype=np.float32)
+    max_blocks = max(pages_per_seg)
+    bt = np.zeros((len(segs), max_blocks), dtype=np.int32)
+    at = 0
+    for i, (req, start, n) in enumerate(segs):
+        bt[i, :pages_per_seg[i]] = np.arange(at, at + pages_per_seg[i])
+        at += pages_per_seg[i]
+        if start > 0:
+            kc = ks[req][:start].float().numpy()
+            vc = vs[req][:start].float().numpy()
+            oracle.kv_append(kc, vc, pool, bt[i:i + 1], [0, start], [0])
+    cu, ctx = opacker.chunk_arrays(segs)
+    return oracle.chunk_prefill_attn_samples(q_chunk, k_chunk, v_chunk, pool, bt, cu, ctx, w.scale, rows, heads)

@@ -1,0 +1,103 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+packed: every output element and the whole pool.  heavy and gqa: sampled (row, head) outputs the oracle
+computes one by one from the same seeded inputs, plus closed-form checks of the pool (each request's pages hold
+exactly its K and V, every other page keeps the sentinel).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import packer as opacker
+from paper_2401_11181_amd import synth
+from paper_2401_11181_amd.prefill import ChunkedPrefill
+import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+DEV = gc.DEV
+
+
+def test_packed_config_full(oracle):
+    """64 chunks of 512 rows packed from 286 lognormal prompts: all outputs, whole pool."""
+    w = synth.workload("packed")
+    qs, ks, vs, tables = gc.workload_tensors(w)
+    outs, pool, sess, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
+    assert sess.n_chunks == 64
+    ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
+    print(gc.compare(outs, ref, label="packed"))
+    bits = gc.oracle_pool_bits(oracle, w, ks, vs, tables)
+    assert np.array_equal(pool.cpu().view(torch.int16).numpy().view(np.uint16), bits)
+    # the sharp distribution on the same plan
+    ws = synth.sharp(w)
+    ws.seed = 2003
+    qs, ks, vs, _ = gc.workload_tensors(ws)
+    outs, _, _, _ = gc.gpu_prefill(ws, qs, ks, vs, tables)
+    ref, _, _ = gc.oracle_prefill(oracle, ws, qs, ks, vs, tables)
+    print(gc.compare(outs, ref, label="packed-sharp"))
+
+
+def run_sampled(oracle, w, check_chunks, n_samples, seed):
+    """Run the whole workload on the GPU; check sampled outputs of the given chunks and the pool."""
+    qs, ks, vs, tables = gc.workload_tensors(w)
+    sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                          w.num_pages, tables, device=DEV, page_size=w.page_size)
+    plan = opacker.pack_chunks(w.prompt_lens, w.order, w.chunk_size)
+    assert [sess.chunk_segments(c) for c in range(sess.n_chunks)] == [list(c) for c in plan]
+    pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
+    dq = [t.to(DEV) for t in qs]
+    dk = [t.to(DEV) for t in ks]
+    dv = [t.to(DEV) for t in vs]
+    rng = np.random.default_rng(seed)
+    check_chunks = [c % sess.n_chunks for c in check_chunks]
+    worst = dict(max_abs=0.0, mean_abs=0.0, rel_l2=0.0)
+    for c in range(sess.n_chunks):
+        q, k, v = sess.gather_chunk(dq, c), sess.gather_chunk(dk, c), sess.gather_chunk(dv, c)
+        out = torch.full((w.chunk_size, w.num_q_heads, w.head_dim), 7.0, dtype=torch.bfloat16, device=DEV)
+        sess.attn(c, q, k, v, pool, w.scale, out)
+        sess.append(c, k, v, pool)
+        if c not in check_chunks:
+            continue
+        sess.validate(c)
+        segs = plan[c]
+        n_real = sum(n for _, _, n in segs)
+        rows = rng.integers(0, n_real, size=n_samples).astype(np.int32)
+        rows[0], rows[1] = 0, n_real - 1
+        heads = rng.integers(0, w.num_q_heads, size=n_samples).astype(np.int32)
+        ref = gc.oracle_chunk_samples(oracle, w, segs, q.float().cpu().numpy(), k.float().cpu().numpy(),
+                                      v.float().cpu().numpy(), ks, vs, rows, heads)
+        got = out.float().cpu().numpy()[rows, heads]
+        assert not out[n_real:].any()
+        err = np.abs(got - ref)
+        rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        assert np.isfinite(got).all()
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3 and rel <= 1e-2, (c, err.max(), err.mean(), rel)
+        worst = dict(max_abs=max(worst["max_abs"], err.max()), mean_abs=max(worst["mean_abs"], err.mean()),
+                     rel_l2=max(worst["rel_l2"], rel))
+    torch.cuda.synchronize()
+    # pool closed form: each request's pages hold exactly its K and V in token order ...
+    P = w.page_size
+    touched = torch.zeros(w.num_pages, dtype=torch.bool, device=DEV)
+    for r, n in enumerate(w.prompt_lens):
+        pages = torch.from_numpy(tables[r].astype(np.int64)).to(DEV)
+        touched[pages] = True
+        blk = pool[pages]                                        # [pages, 2, Hkv, P, D]
+        for which, src in ((0, dk[r]), (1, dv[r])):
+            got = blk[:, which].permute(0, 2, 1, 3).reshape(-1, w.num_kv_heads, w.head_dim)
+            assert torch.equal(got[:n].view(torch.int16), src.view(torch.int16)), (r, which)
+            if n % P:                                            # the unused tail of the last page
+                assert (got[n:].view(torch.int16) == 0x3B5A).all()
+    # ... and every other page still holds the sentinel
+    assert (pool[~touched].view(torch.int16) == 0x3B5A).all()
+    return worst
+
+
+def test_heavy_config_sampled(oracle):
+    """One 16384-token prompt in 32 chunks, pages scattered over a 32768-page pool (10.7 GB)."""
+    w = synth.workload("heavy")
+    print(run_sampled(oracle, w, check_chunks=[0, 1, 15, 30, 31], n_samples=48, seed=4))
+
+
+def test_gqa_config_sampled(oracle):
+    """8 prompts of 4k..32k tokens, 32 query heads on 8 kv heads, ChunkSize 2048, packed chunks."""
+    w = synth.workload("gqa")
+    print(run_sampled(oracle, w, check_chunks=[0, 8, 9, 30, 50, -2, -1], n_samples=32, seed=5))

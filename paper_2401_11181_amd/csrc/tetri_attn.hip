@@ -296,8 +296,27 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         int kb = 0;
         bf16x8 kf[KSTEPS];
         load_k(kf, kq * kBNW, smem + (it & 1) * 2 * STAGE_U4);
-        f32x16 s_cur = qk(kf);
-        for (;;) {
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+        // weights of a block from its scores and the row's reference exponent m: bf16-rounded, laid out
+        // as the B operand of the PV product; returns this lane's sum of the rounded weights (the row
+        // sum is taken over the weights the PV product uses)
+        auto weights = [&](const f32x16 &sc, bf16x8 (&pf)[2]) -> float {
+            float l_blk = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                bf16x2 pp;
+                pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], c, -m));
+                pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v + 1], c, -m));
+                l_blk = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_blk, false);
+                pf[v / 8][v % 8] = pp[0];
+                pf[v / 8][v % 8 + 1] = pp[1];
+            }
+            return l_blk;
+        };
+        // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
+        // after the last block.
+        auto block = [&](f32x16 &s_cur, f32x16 &s_next) -> bool {
             const bool is_ctx = it < ks.n_ctx_tiles;
             const int key0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
             const int row0 = kq * kBNW + kb * 32;
@@ -321,9 +340,8 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 have_next = it < n_stages;
             }
             if (have_next) load_k(kf, kq * kBNW + kb * 32, smem + (it & 1) * 2 * STAGE_U4);
-            // ---- this block's scores: mask, row max.  Accumulator element v is key
-            // key0 + (v/4)*8 + 4*half + v%4; keys past `bound` (the end of the cached context, or the
-            // query's own position) get weight exp2(-inf) = 0.
+            // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
+            // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
             if (need_mask) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -331,13 +349,30 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                     if (key > bound) s_cur[v] = -INFINITY;
                 }
             }
-            float mx = s_cur[0];
+            // ---- one straight-line region: the scores of the next block (discarded after the last
+            // one) on the matrix cores, interleaved with exponentiating and rounding this block's
+            // weights on the VALU, against the reference exponent m the row already has
+            __builtin_amdgcn_sched_barrier(0);
+            s_next = qk(kf);
+            bf16x8 pf[2];
+            float l_blk = weights(s_cur, pf);
+            // wanted order: one MFMA of the score chain, then its share of the VALU operations, 8 times
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
-            mx = half_swap_max(mx) * c;
-            // The running max is only raised when a row's block maximum exceeds it by more than 2^8, so
-            // weights stay below 2^8 and O is rescaled rarely.
-            if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
+            for (int g = 0; g < KSTEPS; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- m is only a reference point, not the exact row maximum: any value keeps the result
+            // exact as long as the weights stay in range.  Only when a lane's weights of this block
+            // sum to more than 2^16 (or overflowed: first block, or scores far above anything seen
+            // before) is m raised to the true maximum, O and the row sum rescaled in place, and the
+            // weights recomputed.  The two half-waves of a row take the same decision.
+            if (__builtin_amdgcn_ballot_w64(!(l_blk <= 65536.0f)) != 0) {
+                float mx = s_cur[0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
+                mx = half_swap_max(mx) * c;
                 const float m_new = fmaxf(m, mx);
                 float alpha = __builtin_amdgcn_exp2f(m - m_new);
                 // the wait state a transcendental result needs before a VALU use; the compiler does not
@@ -345,45 +380,25 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 asm volatile("s_nop 1" : "+v"(alpha));
                 m = m_new;
                 lsum *= alpha;
-                // in place, so that the accumulators keep their registers on both paths
 #pragma unroll
                 for (int i = 0; i < DBLK; ++i)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(o[i][v]) : "v"(alpha));
+                l_blk = weights(s_cur, pf);
             }
-            // ---- one straight-line region: the scores of the next block (discarded after the last
-            // one) on the matrix cores, interleaved with exponentiating and rounding this block's
-            // weights on the VALU; then O^T += V^T P^T.
-            __builtin_amdgcn_sched_barrier(0);
-            const f32x16 s_next = qk(kf);
-            bf16x8 pf[2];
-            bf16x2 ones;
-            ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                bf16x2 pp;
-                pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[v], c, -m));
-                pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[v + 1], c, -m));
-                // the row sum is taken over the rounded weights, the ones the PV product uses
-                lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
-                pf[v / 8][v % 8] = pp[0];
-                pf[v / 8][v % 8 + 1] = pp[1];
-            }
-            // Step j contracts the 16 keys held in accumulator elements 8j..8j+7
+            lsum += l_blk;
+            // ---- O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
-            // wanted order: one MFMA of the score chain, then 6 VALU operations of the softmax, 8 times
-#pragma unroll
-            for (int g = 0; g < KSTEPS; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (!have_next) break;
-            s_cur = s_next;
+            return have_next;
+        };
+        f32x16 s_a = qk(kf), s_b;
+        for (;;) {
+            if (!block(s_a, s_b)) break;
+            if (!block(s_b, s_a)) break;
         }
     }
 

@@ -30,6 +30,7 @@ def main():
     ap.add_argument("--workload", default="opt13b", choices=["tiny", "opt13b", "packed", "heavy", "gqa"])
     ap.add_argument("--mode", default="eager", choices=["graph", "eager"])
     ap.add_argument("--settle", type=float, default=0.5, help="seconds of untimed steps before the warmup")
+    ap.add_argument("--two-launches", action="store_true", help="separate attention and append launches per chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
     args = ap.parse_args()
@@ -53,7 +54,7 @@ def main():
     tables = synth.place_pages(w)
     pipe = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                            w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
-                           use_graph=(args.mode == "graph"))
+                           use_graph=(args.mode == "graph"), fused=not args.two_launches)
     if args.variant is not None:
         pipe.handle.tetri_set_option("attn_variant", args.variant)
     nC, C = pipe.n_chunks, w.chunk_size
@@ -130,7 +131,8 @@ def main():
     pipe.host_plan(0)
     pipe.meta_dev.copy_(pipe.stage[0])
     torch.cuda.synchronize()
-    attn_ms = np.array([group_time(lambda c=c: pipe.launch_attn(c)) for c in range(min(nC, 64))])
+    main_launch = pipe.launch_attn if args.two_launches else pipe.launch_fused
+    attn_ms = np.array([group_time(lambda c=c: main_launch(c)) for c in range(min(nC, 64))])
     app_ms = np.array([group_time(lambda c=c: pipe.launch_append(c)) for c in range(min(nC, 8))])
     n_meas = len(attn_ms)
     attn_avg_ms = float(attn_ms.mean())                 # average duration of one attention launch
@@ -161,10 +163,11 @@ def main():
                                                            w.num_q_heads, w.head_dim, w.num_kv_heads, w.page_size,
                                                            w.seed),
             "chunk_size": C, "launch_mode": args.mode,
-            "step": "pack + metadata + upload + per chunk (attention, kv append)",
+            "step": "pack + metadata + upload + per chunk " +
+                    ("(attention launch, kv append launch)" if args.two_launches else "one fused attention+append launch"),
         },
         "roofline": {
-            "bound": "mfma", "kernel": "attn_fwd_kernel",
+            "bound": "mfma", "kernel": "attn_tile_kernel" + ("" if args.two_launches else " (with fused kv append)"),
             "achieved": round(achieved_tflops, 3), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved_tflops / PEAK_BF16_MFMA_TFLOPS, 5),
             "avg_launch_ms": round(attn_avg_ms, 5), "flops_per_launch": attn_flops_per_launch,
@@ -175,7 +178,7 @@ def main():
             "attn_tflops": [round(flops[c] / (float(attn_med[c]) * 1e-3) / 1e12, 2) for c in range(len(attn_med))],
             "append_ms_median": [round(float(x), 5) for x in app_med],
         },
-        "append": {"avg_launch_ms": round(app_avg_ms, 5),
+        "append": {"kernel": "kv_append_kernel (stand-alone launch)", "avg_launch_ms": round(app_avg_ms, 5),
                    "achieved_GBs": round(app_bytes / (app_avg_ms * 1e-3) / 1e9, 1), "peak_GBs": PEAK_HBM_GBS,
                    "frac": round(app_bytes / (app_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }

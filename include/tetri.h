@@ -186,6 +186,19 @@ TETRI_API tetri_status tetri_chunk_prefill_attn(tetri_ctx *ctx, const void *q, c
                                       void *out, void *stream);
 
 /*
+ * Attention and KV append of one chunk in ONE launch (the two steps of Sec. 3.3.3's per-chunk
+ * forward that touch the KV cache).  Same results, bit for bit, as tetri_chunk_prefill_attn followed
+ * by tetri_kv_append with the same arguments: attention reads only positions < ctx_lens[s] from
+ * the pool, the append writes only positions >= ctx_lens[s], so the two do not interfere.
+ * Arguments as tetri_chunk_prefill_attn, except that kv_pages is in/out.
+ */
+TETRI_API tetri_status tetri_chunk_prefill_attn_append(tetri_ctx *ctx, const void *q, const void *k_new,
+                                                       const void *v_new, void *kv_pages,
+                                                       const int32_t *block_table, const int32_t *cu_chunk_q_lens,
+                                                       const int32_t *ctx_lens, int32_t num_segs, float scale,
+                                                       void *out, void *stream);
+
+/*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
  * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
  * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages

@@ -122,6 +122,35 @@ __device__ __forceinline__ int load_stage_page(const KeySource &ks, int it, int 
     return bt[min(it * (kBNW * KS / kPage) + wave, ks.max_blocks - 1)];   // clamped entries are never used
 }
 
+// Fused KV append: workgroup `blk` of `nblk` copies chunk rows blk, blk + nblk, ... (K and V of
+// every kv head, 16 bytes per thread and pass) into slot (ctx + t) % 16 of page
+// block_table[s][(ctx + t) / 16].  Same result as the stand-alone append kernel, bit for bit.
+template <int D>
+__device__ __forceinline__ void append_rows(const AttnParams &p, int blk, int nblk, int tid, int nthreads)
+{
+    constexpr int CH = D / 8;
+    const int n_real = p.cu[p.S];
+    const int per_row = p.Hkv * CH;                    // 16-byte vectors per row and matrix
+    for (int row = blk; row < n_real; row += nblk) {
+        int lo = 0, hi = p.S - 1;                      // largest s with cu[s] <= row (uniform)
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (p.cu[mid] <= row) lo = mid; else hi = mid - 1;
+        }
+        const int pos = p.ctx[lo] + (row - p.cu[lo]);
+        const int page = p.bt[(size_t)lo * p.max_blocks + pos / kPage];
+        const int slot = pos % kPage;
+        for (int x = tid; x < 2 * per_row; x += nthreads) {
+            const int which = x >= per_row, y = x - which * per_row;
+            const int head = y / CH, c = y - head * CH;
+            const uint4 *src = reinterpret_cast<const uint4 *>(which ? p.v_new : p.k_new) + (size_t)row * per_row + y;
+            uint4 *dst = reinterpret_cast<uint4 *>(p.pages_w) +
+                         (((size_t)page * 2 + which) * p.Hkv + head) * (kPage * CH) + (size_t)slot * CH + c;
+            *dst = *src;
+        }
+    }
+}
+
 template <int D, int KS>
 __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
 {
@@ -141,21 +170,44 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int BM = 32 * p.rb;
     const int S = p.S;
 
+    // ---- workgroups past the attention grid copy the chunk's new K/V rows into their page slots
+    // (fused KV append; they land on CUs the attention grid leaves idle or finish in its tail)
+    if ((int)blockIdx.x >= p.attn_grid) {
+        append_rows<D>(p, blockIdx.x - p.attn_grid, gridDim.x - p.attn_grid, tid, kSlots * KS * 64);
+        return;
+    }
     // ---- workgroup id -> (head group, row tile); a head group's tiles share one XCD
-    const int per_xcd = gridDim.x / kXcd;
+    const int per_xcd = p.attn_grid / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
     const int groups = p.Hq / p.hpw;
     if (logical >= p.tiles * groups) return;
     const int grp = logical / p.tiles;
     int tile = p.tiles - 1 - logical % p.tiles;        // late (long) tiles first
 
-    // ---- which (segment, row tile) is it?  Tiles never span two segments.
-    int s = 0, t0 = -1;
-    for (; s < S; ++s) {
-        const int n = p.cu[s + 1] - p.cu[s];
-        const int nt = (n + BM - 1) / BM;
-        if (tile < nt) { t0 = tile * BM; break; }
-        tile -= nt;
+    // ---- which (segment, row tile) is it?  Tiles never span two segments.  64 segments are
+    // examined at a time: lane l takes segment s0 + l, a wave-wide prefix sum of the tile counts
+    // finds the segment that owns `tile`.
+    int s = -1, t0 = -1, seg_cu = 0, n_s = 0;
+    for (int s0 = 0; s0 < S; s0 += 64) {
+        const int idx = s0 + lane;
+        const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
+        const int nt = (b - a + BM - 1) / BM;          // 0 for lanes past the last segment
+        int incl = nt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        const unsigned long long owner = __builtin_amdgcn_ballot_w64(tile >= incl - nt && tile < incl);
+        if (owner != 0) {
+            const int src = __builtin_ctzll(owner);
+            s = s0 + src;
+            t0 = (tile - __builtin_amdgcn_readlane(incl - nt, src)) * BM;
+            seg_cu = __builtin_amdgcn_readlane(a, src);
+            n_s = __builtin_amdgcn_readlane(b - a, src);
+            break;
+        }
+        tile -= __builtin_amdgcn_readlane(incl, 63);
     }
     const int hh = slot % p.hpw, rbk = slot / p.hpw;
     const int head = grp * p.hpw + hh;
@@ -170,11 +222,11 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         }
         return;
     }
-    const int n_s = p.cu[s + 1] - p.cu[s], L = p.ctx[s];
+    const int L = ((const const_i32 *)(uintptr_t)p.ctx)[s];
     KeySource ks;
     ks.pages = p.pages; ks.k_new = p.k_new; ks.v_new = p.v_new;
     ks.bt_row = p.bt + (size_t)s * p.max_blocks;
-    ks.Hkv = p.Hkv; ks.kh = (grp * p.hpw) / p.g; ks.row_base = p.cu[s]; ks.L = L;
+    ks.Hkv = p.Hkv; ks.kh = (grp * p.hpw) / p.g; ks.row_base = seg_cu; ks.L = L;
     ks.n_new = min(n_s, t0 + BM);                      // new keys any row of this tile may see
     ks.n_ctx_tiles = (L + STAGE - 1) / STAGE;
     ks.max_blocks = p.max_blocks;
@@ -444,10 +496,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
 template <int D, int KS>
 hipError_t launch(const AttnParams &p, hipStream_t stream)
 {
-    const int groups = p.Hq / p.hpw;
-    const int nwg = p.tiles * groups;
-    const int grid = (nwg + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((attn_tile_kernel<D, KS>), dim3(grid), dim3(kSlots * KS * 64), 0, stream, p);
+    hipLaunchKernelGGL((attn_tile_kernel<D, KS>), dim3(p.attn_grid + p.append_blocks), dim3(kSlots * KS * 64), 0, stream, p);
     return hipGetLastError();
 }
 

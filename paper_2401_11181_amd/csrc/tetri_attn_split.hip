@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kSplit * 64, 2) void attn_split_kernel(AttnParams p
     const int S = p.S;
 
     // ---- workgroup id -> (head, 32-row block); all row blocks of a head share one XCD
-    const int per_xcd = gridDim.x / kXcd;
+    const int per_xcd = p.attn_grid / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
     if (logical >= p.tiles * p.Hq) return;
     const int head = logical / p.tiles;
@@ -264,9 +264,7 @@ __global__ __launch_bounds__(kSplit * 64, 2) void attn_split_kernel(AttnParams p
 template <int D>
 hipError_t launch_split(const AttnParams &p, hipStream_t stream)
 {
-    const int nwg = p.tiles * p.Hq;
-    const int grid = (nwg + kXcd - 1) / kXcd * kXcd;
-    hipLaunchKernelGGL((attn_split_kernel<D>), dim3(grid), dim3(kSplit * 64), 0, stream, p);
+    hipLaunchKernelGGL((attn_split_kernel<D>), dim3(p.attn_grid), dim3(kSplit * 64), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -243,43 +243,66 @@ tetri_status tetri_kv_append(tetri_ctx *h, const void *k_new, const void *v_new,
     return TETRI_OK;
 }
 
-tetri_status tetri_chunk_prefill_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
-                                      const void *kv_pages, const int32_t *block_table, const int32_t *cu,
-                                      const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)
+static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                const void *kv_pages, void *kv_pages_w, const int32_t *block_table, const int32_t *cu,
+                                const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)
 {
     const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
     const char *names[] = {"q", "k_new", "v_new", "kv_pages", "out"};
-    tetri_status st = check_common(h, "tetri_chunk_prefill_attn", ptrs, names, 5, num_segs);
+    tetri_status st = check_common(h, fn, ptrs, names, 5, num_segs);
     if (st != TETRI_OK) return st;
-    if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_chunk_prefill_attn: null metadata pointer");
-    if (!std::isfinite(scale)) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_chunk_prefill_attn: scale is not finite");
+    if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "%s: null metadata pointer", fn);
+    if (!std::isfinite(scale)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: scale is not finite", fn);
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
     p.k_new = static_cast<const uint16_t *>(k_new);
     p.v_new = static_cast<const uint16_t *>(v_new);
     p.pages = static_cast<const uint16_t *>(kv_pages);
+    p.pages_w = static_cast<uint16_t *>(kv_pages_w);
     p.bt = block_table; p.cu = cu; p.ctx = ctx_lens;
     p.out = static_cast<uint16_t *>(out);
     p.S = num_segs; p.C = h->cfg.chunk_size; p.Hq = h->cfg.num_q_heads; p.Hkv = h->cfg.num_kv_heads;
     p.g = p.Hq / p.Hkv;
-    wave_grouping(p.g, &p.hpw, &p.rb);
-    p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
     p.max_blocks = h->cfg.max_blocks_per_seq;
     // scale == 0 is run as a tiny positive scale: every finite score then maps to weight 1 exactly,
     // while masked scores (-inf) still map to weight 0
     p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     p.neg = scale < 0.f;
-    hipError_t e;
-    if (h->attn_variant == 3) {
+    const bool split = h->attn_variant == 3 && !kv_pages_w;
+    if (split) {
         // key-split kernel: one workgroup per (head, 32-row block)
         p.hpw = 1; p.rb = 1;
         p.tiles = tile_bound(p.C, p.S, 32);
-        e = tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream));
+        p.attn_grid = (p.tiles * p.Hq + 7) / 8 * 8;
+        p.append_blocks = 0;
     } else {
-        e = tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));
+        wave_grouping(p.g, &p.hpw, &p.rb);
+        p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
+        p.attn_grid = (p.tiles * (p.Hq / p.hpw) + 7) / 8 * 8;
+        // fused append: a few dozen workgroups, each copying every 64th row of the chunk
+        p.append_blocks = kv_pages_w ? (p.C < 64 ? p.C : 64) : 0;
     }
-    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "tetri_chunk_prefill_attn: launch failed: %s", hipGetErrorString(e));
+    hipError_t e = split ? tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream))
+                         : tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;
+}
+
+tetri_status tetri_chunk_prefill_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                      const void *kv_pages, const int32_t *block_table, const int32_t *cu,
+                                      const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)
+{
+    return attn_common("tetri_chunk_prefill_attn", h, q, k_new, v_new, kv_pages, nullptr, block_table, cu, ctx_lens,
+                       num_segs, scale, out, stream);
+}
+
+tetri_status tetri_chunk_prefill_attn_append(tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                             void *kv_pages, const int32_t *block_table, const int32_t *cu,
+                                             const int32_t *ctx_lens, int32_t num_segs, float scale, void *out,
+                                             void *stream)
+{
+    return attn_common("tetri_chunk_prefill_attn_append", h, q, k_new, v_new, kv_pages, kv_pages, block_table, cu,
+                       ctx_lens, num_segs, scale, out, stream);
 }
 
 tetri_status tetri_validate_chunk(tetri_ctx *h, const int32_t *block_table, const int32_t *cu, const int32_t *ctx_lens,

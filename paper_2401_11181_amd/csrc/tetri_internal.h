@@ -17,11 +17,14 @@ struct AttnParams {
     const uint16_t *q, *k_new, *v_new, *pages;   // bf16 bit patterns
     const int32_t *bt, *cu, *ctx;
     uint16_t *out;
+    uint16_t *pages_w;    // pool for the fused append (null when append_blocks == 0)
     int32_t S, C, Hq, Hkv, g;
     int32_t hpw;          // query heads handled by one workgroup (they share one kv head)
     int32_t rb;           // 32-row blocks handled by one workgroup
     int32_t max_blocks;
     int32_t tiles;        // upper bound of the number of row tiles of the chunk
+    int32_t attn_grid;    // workgroups of the attention grid (a multiple of 8)
+    int32_t append_blocks; // extra workgroups that do the fused KV append (0: none)
     float c;              // |scale| * log2(e)
     int32_t neg;          // 1 if scale < 0
 };

@@ -79,6 +79,10 @@ class ChunkedPrefill:
         cu, ctx, bt, S = self.meta[c]
         self.handle.tetri_kv_append(k_new, v_new, kv_pages, bt, cu, ctx, S, stream)
 
+    def attn_append(self, c, q, k_new, v_new, kv_pages, scale, out, stream=None):
+        cu, ctx, bt, S = self.meta[c]
+        self.handle.tetri_chunk_prefill_attn_append(q, k_new, v_new, kv_pages, bt, cu, ctx, S, scale, out, stream)
+
     def validate(self, c):
         cu, ctx, bt, S = self.meta[c]
         self.handle.tetri_validate_chunk(bt, cu, ctx, S)
@@ -97,7 +101,8 @@ class PrefillPipeline:
 
     step() = pack the batch into chunks and build every chunk's metadata on the host
     (tetri_plan_metadata, one C call) into pinned memory, one asynchronous upload, then for every
-    chunk in order one attention launch and one append launch (Sec. 3.3.3: one chunk at a time; the
+    chunk in order one launch that does attention and append (or two launches with fused=False;
+    Sec. 3.3.3: one chunk at a time; the
     progress variable of each request is the `start` field of its next segment).
     Inputs (per-chunk q, k_new, v_new) and the page pool are resident in HBM before a step.
     With use_graph the launches of a step are replayed from a HIP graph; packing, metadata and the
@@ -107,10 +112,11 @@ class PrefillPipeline:
     RING = 4    # pinned staging buffers in flight
 
     def __init__(self, prompt_lens, order, chunk_size, num_q_heads, num_kv_heads, head_dim, num_pages,
-                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False):
+                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False, fused=True):
         self.device = torch.device(device)
         self.C, self.Hq, self.Hkv, self.D = chunk_size, num_q_heads, num_kv_heads, head_dim
         self.scale = float(scale)
+        self.fused = fused          # one launch per chunk (attention + append) instead of two
         self.lens = np.ascontiguousarray(prompt_lens, dtype=np.int32)
         self.order = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
         self.max_blocks = max(1, max(len(t) for t in req_block_tables))
@@ -170,6 +176,12 @@ class PrefillPipeline:
         if rc != tetri.TETRI_OK:
             raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
 
+    def launch_fused(self, c, stream=None):
+        """Attention and append of chunk c in one launch."""
+        rc = self._lib.tetri_chunk_prefill_attn_append(*self._attn_args[c], stream or tetri._stream(None))
+        if rc != tetri.TETRI_OK:
+            raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
+
     def launch_append(self, c, stream=None):
         rc = self._lib.tetri_kv_append(*self._app_args[c], stream or tetri._stream(None))
         if rc != tetri.TETRI_OK:
@@ -178,8 +190,11 @@ class PrefillPipeline:
     def _launch_all(self):
         stream = tetri._stream(None)                # the current stream, looked up once per step
         for c in range(self.n_chunks):
-            self.launch_attn(c, stream)
-            self.launch_append(c, stream)
+            if self.fused:
+                self.launch_fused(c, stream)
+            else:
+                self.launch_attn(c, stream)
+                self.launch_append(c, stream)
 
     def step(self):
         slot = self.turn % self.RING

@@ -69,6 +69,8 @@ def lib():
         L.tetri_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.tetri_chunk_prefill_attn.restype = i32
         L.tetri_chunk_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+        L.tetri_chunk_prefill_attn_append.restype = i32
+        L.tetri_chunk_prefill_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
         L.tetri_validate_chunk.restype = i32
         L.tetri_validate_chunk.argtypes = [vp, vp, vp, vp, i32, vp]
         L.tetri_set_option.restype = i32
@@ -204,6 +206,12 @@ class Tetri:
         self._check(lib().tetri_chunk_prefill_attn(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
                                                    _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),
                                                    int(num_segs), float(scale), _ptr(out), _stream(stream)))
+
+    def tetri_chunk_prefill_attn_append(self, q, k_new, v_new, kv_pages, block_table, cu_chunk_q_lens, ctx_lens,
+                                        num_segs, scale, out, stream=None):
+        self._check(lib().tetri_chunk_prefill_attn_append(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
+                                                          _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),
+                                                          int(num_segs), float(scale), _ptr(out), _stream(stream)))
 
     def tetri_validate_chunk(self, block_table, cu_chunk_q_lens, ctx_lens, num_segs, stream=None):
         self._check(lib().tetri_validate_chunk(self.h, _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),

@@ -18,7 +18,7 @@ def workload_tensors(w):
     return qs, ks, vs, synth.place_pages(w)
 
 
-def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False, variant=0):
+def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False, variant=0, fused=False):
     """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
     sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                           w.num_pages, tables, device=DEV, page_size=w.page_size)
@@ -37,7 +37,9 @@ def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_c
         if pad_fill is not None and n_real < w.chunk_size:
             q[n_real:], k[n_real:], v[n_real:] = pad_fill, pad_fill, pad_fill
         out = torch.full((w.chunk_size, w.num_q_heads, w.head_dim), 7.0, dtype=torch.bfloat16, device=DEV)
-        if append_first:
+        if fused:
+            sess.attn_append(c, q, k, v, pool, w.scale, out)
+        elif append_first:
             sess.append(c, k, v, pool)
             sess.attn(c, q, k, v, pool, w.scale, out)
         else:

@@ -74,6 +74,31 @@ def test_append_before_attention_gives_same_result(oracle, variant):
     assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
 
 
+@pytest.mark.parametrize("name", ["mid-page-starts", "ragged-tiles", "gqa4", "one-token-segments", "partial-last-chunk"])
+def test_fused_attention_append_equals_two_calls(oracle, name):
+    """tetri_chunk_prefill_attn_append == tetri_chunk_prefill_attn then tetri_kv_append, bit for bit."""
+    lens, chunk, hq, hkv, d = CASES[name]
+    w = synth.small(name, lens, chunk, hq, hkv, d, seed=140)
+    qs, ks, vs, tables = gc.workload_tensors(w)
+    a, pool_a, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
+    b, pool_b, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, fused=True)
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+    assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
+    ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
+    gc.compare(b, ref, label="fused-" + name)
+
+
+def test_fused_opt13b(oracle):
+    w = synth.workload("opt13b")
+    qs, ks, vs, tables = gc.workload_tensors(w)
+    outs, pool, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, fused=True)
+    ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
+    print(gc.compare(outs, ref, label="fused-opt13b"))
+    bits = gc.oracle_pool_bits(oracle, w, ks, vs, tables)
+    assert np.array_equal(pool.cpu().view(torch.int16).numpy().view(np.uint16), bits)
+
+
 @pytest.mark.parametrize("fill", [3.0e4, float("nan")])
 def test_padding_rows_are_inert(oracle, fill, variant):
     w = synth.small("pad", [100, 37], 64, 2, 2, 128, seed=131)

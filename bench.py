@@ -20,6 +20,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
+# plain copy of known size (figures and commands: profiles/attn_tile_kernel_opt13b_hbm_traffic.md)
+MEASURED_TRAFFIC_BYTES = {("opt13b", "fused"): 57.1e6}
 
 
 def main():
@@ -31,6 +34,8 @@ def main():
     ap.add_argument("--mode", default="eager", choices=["graph", "eager"])
     ap.add_argument("--settle", type=float, default=0.5, help="seconds of untimed steps before the warmup")
     ap.add_argument("--two-launches", action="store_true", help="separate attention and append launches per chunk")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="finish with one 256 MiB device-to-device copy (known traffic, to calibrate HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
     args = ap.parse_args()
@@ -171,7 +176,9 @@ def main():
             "achieved": round(achieved_tflops, 3), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved_tflops / PEAK_BF16_MFMA_TFLOPS, 5),
             "avg_launch_ms": round(attn_avg_ms, 5), "flops_per_launch": attn_flops_per_launch,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "two" if args.two_launches else "fused")),
+            "algorithmic_bytes_per_launch": float(np.mean([pipe.attn_bytes(c) + (0 if args.two_launches else
+                                                           pipe.append_bytes(c)) for c in range(n_meas)])),
         },
         "per_chunk": {
             "attn_ms_median": [round(float(x), 5) for x in attn_med],
@@ -232,6 +239,12 @@ def main():
             result["parity_check"] = {"max_abs_vs_oracle": round(worst, 6), "chunks": min(n_done, nC)}
         else:
             result["cpu_baseline"] = None
+    if args.calib_copy:
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        b = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        a.copy_(b)
+        torch.cuda.synchronize()
     print(json.dumps(result))
     return 0
 

@@ -120,6 +120,20 @@ TETRI_API int32_t tetri_pack_chunks(const int32_t *prompt_lens, int32_t n_prompt
                           int32_t *n_segs_out);
 
 /*
+ * Prefill scheduler, host only (Sec. 3.3.2 "Prefill Scheduler"): turns the raw request queue (arrival
+ * order 0..n-1) into the scheduled order that tetri_pack_chunks takes.  Requests are scheduled
+ * sched_batch (PrefillSchedBatch) at a time; inside each group of sched_batch consecutive arrivals
+ * the policy sorts by prompt token count: TETRI_FCFS keeps arrival order, TETRI_SJF ascending,
+ * TETRI_LJF descending.  The sort is stable (ties keep arrival order; the paper uses Python's native
+ * sort).  Non-preemptive: groups are never interleaved.  sched_batch <= 0 means one group of all n.
+ *   prompt_lens [n] host, in; order_out [n] host, out.
+ * Returns TETRI_OK or TETRI_ERR_INVALID_ARG (null pointer, n < 0, unknown policy, negative length).
+ */
+enum { TETRI_FCFS = 0, TETRI_SJF = 1, TETRI_LJF = 2 };
+TETRI_API tetri_status tetri_schedule(const int32_t *prompt_lens, int32_t n, int32_t policy,
+                                      int32_t sched_batch, int32_t *order_out);
+
+/*
  * Per-chunk metadata, host only: turn the segments of one chunk into the three int32 arrays
  * the launching entry points take (the caller then copies them to the device).
  *   segs [num_segs] host; req_block_tables [n_prompts][max_blocks_per_seq] host: page list of

@@ -44,3 +44,25 @@ def chunk_arrays(segs):
         cu.append(cu[-1] + n)
         ctx.append(start)
     return cu, ctx
+
+
+def schedule(prompt_lens, policy, sched_batch):
+    """Scheduled order of the raw queue (Sec. 3.3.2 "Prefill Scheduler").
+
+    The raw queue holds requests 0..n-1 in arrival order.  They are scheduled PrefillSchedBatch at a
+    time; each group is sorted by prompt token count with Python's native (stable) sort: "fcfs" keeps
+    arrival order, "sjf" ascending, "ljf" descending.  Groups are not interleaved (non-preemptive).
+    """
+    n = len(prompt_lens)
+    group = sched_batch if sched_batch and sched_batch > 0 else max(n, 1)
+    order = []
+    for b in range(0, n, group):
+        ids = list(range(b, min(b + group, n)))
+        if policy == "sjf":
+            ids.sort(key=lambda i: prompt_lens[i])
+        elif policy == "ljf":
+            ids.sort(key=lambda i: -prompt_lens[i])
+        elif policy != "fcfs":
+            raise ValueError(policy)
+        order.extend(ids)
+    return order

@@ -1,5 +1,6 @@
 // Host layer of libtetri: handle, argument checks, the chunk packer and the debug validator.
 // TetriInfer Sec. 3.3.3 "Chunked Prefill" is the source of the packing rule.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -147,6 +148,28 @@ int32_t tetri_pack_chunks(const int32_t *prompt_lens, int32_t n_prompts, const i
     if (!query) chunk_seg_offsets[n_chunks] = (int32_t)n_segs;
     if (n_segs_out) *n_segs_out = (int32_t)n_segs;
     return (int32_t)n_chunks;
+}
+
+tetri_status tetri_schedule(const int32_t *prompt_lens, int32_t n, int32_t policy, int32_t sched_batch, int32_t *order_out)
+{
+    if (!prompt_lens || !order_out || n < 0)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: null pointer or negative count");
+    if (policy != TETRI_FCFS && policy != TETRI_SJF && policy != TETRI_LJF)
+        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: unknown policy %d", policy);
+    for (int32_t i = 0; i < n; ++i) {
+        if (prompt_lens[i] < 0) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: prompt_lens[%d]=%d", i, prompt_lens[i]);
+        order_out[i] = i;
+    }
+    if (policy == TETRI_FCFS) return TETRI_OK;
+    const int32_t group = sched_batch > 0 ? sched_batch : (n > 0 ? n : 1);
+    for (int32_t b = 0; b < n; b += group) {
+        int32_t *first = order_out + b, *last = order_out + (b + group < n ? b + group : n);
+        if (policy == TETRI_SJF)
+            std::stable_sort(first, last, [&](int32_t x, int32_t y) { return prompt_lens[x] < prompt_lens[y]; });
+        else
+            std::stable_sort(first, last, [&](int32_t x, int32_t y) { return prompt_lens[x] > prompt_lens[y]; });
+    }
+    return TETRI_OK;
 }
 
 tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t num_segs, const int32_t *req_block_tables,

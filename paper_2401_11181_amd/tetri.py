@@ -60,6 +60,8 @@ def lib():
         L.tetri_last_error.argtypes = [vp]
         L.tetri_pack_chunks.restype = i32
         L.tetri_pack_chunks.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp, i32, ctypes.POINTER(i32)]
+        L.tetri_schedule.restype = i32
+        L.tetri_schedule.argtypes = [vp, i32, i32, i32, vp]
         L.tetri_chunk_metadata.restype = i32
         L.tetri_chunk_metadata.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
         L.tetri_plan_metadata.restype = i32
@@ -124,6 +126,19 @@ def tetri_pack_chunks(prompt_lens, order, chunk_size):
     if rc < 0:
         raise TetriError(rc, tetri_last_error())
     return segs[:n_segs.value], offsets
+
+
+TETRI_FCFS, TETRI_SJF, TETRI_LJF = 0, 1, 2
+
+
+def tetri_schedule(prompt_lens, policy, sched_batch):
+    """tetri_schedule (host).  Returns the scheduled order (int32 array)."""
+    lens = np.ascontiguousarray(prompt_lens, dtype=np.int32)
+    order = np.zeros(len(lens), dtype=np.int32)
+    rc = lib().tetri_schedule(_ptr(lens), len(lens), int(policy), int(sched_batch), _ptr(order))
+    if rc != TETRI_OK:
+        raise TetriError(rc, tetri_last_error())
+    return order
 
 
 def tetri_chunk_metadata(segs, req_block_tables):

@@ -124,3 +124,47 @@ def test_launching_entry_points_reject_a_null_handle():
     assert L.tetri_validate_chunk(None, None, None, None, 1, None) == tetri.TETRI_ERR_INVALID_ARG
     assert L.tetri_set_option(None, b"attn_variant", 0) == tetri.TETRI_ERR_INVALID_ARG
     assert isinstance(tetri.tetri_last_error(), str)
+
+
+# ---------------------------------------------------------------- prefill scheduler (Sec. 3.3.2)
+
+def test_scheduler_paper_example_twenty_requests_batch_ten():
+    """The text's example: twenty queued requests, PrefillSchedBatch 10: two groups, each sorted on its own."""
+    rng = np.random.default_rng(7)
+    lens = [int(x) for x in rng.integers(1, 600, size=20)]
+    for policy, name in ((tetri.TETRI_SJF, "sjf"), (tetri.TETRI_LJF, "ljf"), (tetri.TETRI_FCFS, "fcfs")):
+        order = [int(x) for x in tetri.tetri_schedule(lens, policy, 10)]
+        assert order == opacker.schedule(lens, name, 10)
+        assert sorted(order[:10]) == list(range(10)) and sorted(order[10:]) == list(range(10, 20))
+        first = [lens[i] for i in order[:10]]
+        second = [lens[i] for i in order[10:]]
+        if name == "sjf":
+            assert first == sorted(first) and second == sorted(second)
+        if name == "ljf":
+            assert first == sorted(first, reverse=True) and second == sorted(second, reverse=True)
+        if name == "fcfs":
+            assert order == list(range(20))
+
+
+def test_scheduler_is_stable_and_ljf_is_not_reversed_sjf():
+    lens = [5, 3, 5, 3, 9]
+    assert list(tetri.tetri_schedule(lens, tetri.TETRI_SJF, 0)) == [1, 3, 0, 2, 4]
+    assert list(tetri.tetri_schedule(lens, tetri.TETRI_LJF, 0)) == [4, 0, 2, 1, 3]      # ties keep arrival order
+    assert list(tetri.tetri_schedule(lens, tetri.TETRI_SJF, 2)) == [1, 0, 3, 2, 4]
+    assert list(tetri.tetri_schedule([], tetri.TETRI_SJF, 4)) == []
+    with pytest.raises(tetri.TetriError):
+        tetri.tetri_schedule(lens, 9, 4)
+    with pytest.raises(tetri.TetriError):
+        tetri.tetri_schedule([1, -2], tetri.TETRI_SJF, 4)
+
+
+def test_scheduler_random_batches_match_python_sort_and_feed_the_packer():
+    rng = np.random.default_rng(8)
+    for _ in range(100):
+        n = int(rng.integers(1, 40))
+        lens = [int(x) for x in rng.integers(0, 50, size=n)]
+        batch = int(rng.integers(0, 12))
+        for policy, name in ((tetri.TETRI_SJF, "sjf"), (tetri.TETRI_LJF, "ljf")):
+            order = [int(x) for x in tetri.tetri_schedule(lens, policy, batch)]
+            assert order == opacker.schedule(lens, name, batch)
+            assert lib_plan(lens, order, 16) == [list(c) for c in opacker.pack_chunks(lens, order, 16)]

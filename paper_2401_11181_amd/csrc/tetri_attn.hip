@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     constexpr int NKB = kBNW / 32;   // 32-key blocks of S^T per wavefront per stage
     constexpr int STAGE = kBNW * KS; // keys per stage
     constexpr int STAGE_U4 = STAGE * CH;
-    __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stages: K0 | V0 | K1 | V1
+    __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stage buffers: K0 | K1 | V0 | V1
     __shared__ float Mstat[kSlots][2][32];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     constexpr uint32_t STAGE_BYTES = STAGE_U4 * 16;   // bytes of one matrix of one stage
 
     int page = load_stage_page<KS>(ks, 0, wave);
-    issue_stage_loads<D, KS>(ks, lo, page, 0, wave, lane, new_row_bytes, smem_lds, smem_lds + STAGE_BYTES);
+    issue_stage_loads<D, KS>(ks, lo, page, 0, wave, lane, new_row_bytes, smem_lds, smem_lds + 2 * STAGE_BYTES);
     page = load_stage_page<KS>(ks, 1, wave);
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7]
@@ -271,30 +271,42 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const float c = p.c;
     const int blk = lane >> 4, i16 = lane & 15;
 
-    // Fragment loads from LDS.  K: lane holds key row0 + l32, d = 16*st + 8*half .. +7 (A operand
-    // of S^T).  V: for step j (16 keys) and d block db the lane gets keys row0 + 16j + 4*half +
+    // Fragment loads from LDS.  K: lane holds key (row) l32 of a 32-key block, d = 16*st + 8*half .. +7
+    // (A operand of S^T).  V: for step j (16 keys) and d block db the lane gets keys 16j + 4*half +
     // {0..3, 8..11} of d = 32*db + l32 through two transposing reads (A operand of O^T).
-    auto load_k = [&](bf16x8 (&kf)[KSTEPS], int row0, const uint4 *Kt) {
-        const int r = row0 + l32;
+    // The per-lane parts of the addresses (row inside the wavefront's 64-key part, swizzled chunk)
+    // never change: they are computed once; stage buffer and block are added as one byte offset,
+    // which is an instruction immediate wherever it is known at compile time.
+    constexpr int BLOCK_BYTES = 32 * D * 2;            // one 32-key block of K or of V
+    uint32_t kbase[KSTEPS], vbase[DBLK];
+    {
+        const int r = kq * kBNW + l32;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) kbase[st] = r * D * 2 + (((2 * st + half) ^ k_swizzle<D>(r)) << 4);
+        const int rv = kq * kBNW + 4 * half + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
+            vbase[db] = 2 * STAGE_BYTES + rv * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
+        }
+    }
+    const char *smem_b = reinterpret_cast<const char *>(smem);
+    // off = buffer * STAGE_BYTES + block * BLOCK_BYTES
+    auto load_k = [&](bf16x8 (&kf)[KSTEPS], int off) {
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st)
-            kf[st] = __builtin_bit_cast(bf16x8, Kt[r * CH + ((2 * st + half) ^ k_swizzle<D>(r))]);
+            kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + kbase[st] + off));
     };
-    auto load_v = [&](s16x8 (&vf)[2 * DBLK], int row0, const uint4 *Vt) {
-        const char *vb = reinterpret_cast<const char *>(Vt);
+    auto load_v = [&](s16x8 (&vf)[2 * DBLK], int off) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int ra = row0 + j * 16 + 4 * half + (i16 >> 2), rb2 = ra + 8;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int db = 0; db < DBLK; ++db) {
-                const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
-                const int offa = ra * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(ra)) << 4) + ((d0 & 7) << 1);
-                const int offb = rb2 * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rb2)) << 4) + ((d0 & 7) << 1);
-                const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vb + offa));
-                const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vb + offb));
+                const char *a = smem_b + vbase[db] + off + j * (16 * D * 2);
+                const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
+                const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * D * 2));
                 vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-        }
     };
 
     // Number of 32-key blocks of stage `it` this wavefront works on (a prefix of its 64-key part):
@@ -318,8 +330,8 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         wait_vm<0>();
         __syncthreads();
         if (it + 1 < n_stages) {
-            const uint32_t nb = smem_lds + ((it + 1) & 1) * 2 * STAGE_BYTES;
-            issue_stage_loads<D, KS>(ks, lo, page, it + 1, wave, lane, new_row_bytes, nb, nb + STAGE_BYTES);
+            const uint32_t nb = smem_lds + ((it + 1) & 1) * STAGE_BYTES;
+            issue_stage_loads<D, KS>(ks, lo, page, it + 1, wave, lane, new_row_bytes, nb, nb + 2 * STAGE_BYTES);
         }
         page = load_stage_page<KS>(ks, it + 2, wave);
     };
@@ -347,7 +359,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     if (it < n_stages) {
         int kb = 0;
         bf16x8 kf[KSTEPS];
-        load_k(kf, kq * kBNW, smem + (it & 1) * 2 * STAGE_U4);
+        load_k(kf, (it & 1) * STAGE_BYTES);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
         // weights of a block from its scores and the row's reference exponent m: bf16-rounded, laid out
@@ -366,44 +378,11 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             }
             return l_blk;
         };
-        // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
-        // after the last block.
-        auto block = [&](f32x16 &s_cur, f32x16 &s_next) -> bool {
-            const bool is_ctx = it < ks.n_ctx_tiles;
-            const int key0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
-            const int row0 = kq * kBNW + kb * 32;
-            const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
-            const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
-            // V fragments of this block: in registers before the stage may be left
-            s16x8 vf[2 * DBLK];
-            load_v(vf, row0, smem + (it & 1) * 2 * STAGE_U4 + STAGE_U4);
-            // ---- the block after this one
-            bool have_next = true;
-            if (kb + 1 < nblk) {
-                ++kb;
-            } else {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS
-                kb = 0;
-                nblk = 0;
-                while (nblk == 0 && ++it < n_stages) {
-                    enter_stage(it);
-                    nblk = stage_blocks(it);
-                }
-                have_next = it < n_stages;
-            }
-            if (have_next) load_k(kf, kq * kBNW + kb * 32, smem + (it & 1) * 2 * STAGE_U4);
-            // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
-            // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
-            if (need_mask) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
-                    if (key > bound) s_cur[v] = -INFINITY;
-                }
-            }
-            // ---- one straight-line region: the scores of the next block (discarded after the last
-            // one) on the matrix cores, interleaved with exponentiating and rounding this block's
-            // weights on the VALU, against the reference exponent m the row already has
+        // The second half of a block: scores of the next block (its K fragments
+        // are in kf; discarded after the last block) on the matrix cores, interleaved with
+        // exponentiating and rounding this block's weights on the VALU against the reference exponent
+        // m the row already has; then the PV product with the V fragments in vf.
+        auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, const s16x8 (&vf)[2 * DBLK]) {
             __builtin_amdgcn_sched_barrier(0);
             s_next = qk(kf);
             bf16x8 pf[2];
@@ -415,11 +394,11 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            // ---- m is only a reference point, not the exact row maximum: any value keeps the result
-            // exact as long as the weights stay in range.  Only when a lane's weights of this block
-            // sum to more than 2^16 (or overflowed: first block, or scores far above anything seen
-            // before) is m raised to the true maximum, O and the row sum rescaled in place, and the
-            // weights recomputed.  The two half-waves of a row take the same decision.
+            // m is only a reference point, not the exact row maximum: any value keeps the result exact
+            // as long as the weights stay in range.  Only when a lane's weights of this block sum to
+            // more than 2^16 (or overflowed: first block, or scores far above anything seen before) is
+            // m raised to the true maximum, O and the row sum rescaled in place, and the weights
+            // recomputed.  The two half-waves of a row take the same decision.
             if (__builtin_amdgcn_ballot_w64(!(l_blk <= 65536.0f)) != 0) {
                 float mx = s_cur[0];
 #pragma unroll
@@ -439,12 +418,48 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 l_blk = weights(s_cur, pf);
             }
             lsum += l_blk;
-            // ---- O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
+            // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
+        };
+        // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
+        // after the last block.
+        auto block = [&](f32x16 &s_cur, f32x16 &s_next) -> bool {
+            const bool is_ctx = it < ks.n_ctx_tiles;
+            const int key0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
+            const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
+            const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
+            // V fragments of this block: in registers before the stage may be left
+            s16x8 vf[2 * DBLK];
+            load_v(vf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
+            // ---- the block after this one
+            bool have_next = true;
+            if (kb + 1 < nblk) {
+                ++kb;
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS
+                kb = 0;
+                nblk = 0;
+                while (nblk == 0 && ++it < n_stages) {
+                    enter_stage(it);
+                    nblk = stage_blocks(it);
+                }
+                have_next = it < n_stages;
+            }
+            if (have_next) load_k(kf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
+            // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
+            // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
+            if (need_mask) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
+                    if (key > bound) s_cur[v] = -INFINITY;
+                }
+            }
+            softmax_pv(s_cur, s_next, vf);
             return have_next;
         };
         f32x16 s_a = qk(kf), s_b;

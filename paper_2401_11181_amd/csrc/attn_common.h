@@ -10,6 +10,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_cvoid;
@@ -17,15 +18,51 @@ typedef __attribute__((address_space(1))) const void gbl_cvoid;
 constexpr int kPage = 16;     // tokens per KV page
 constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
 
+// Optional timeline instrumentation (only in builds with -DTETRI_TRACE, never in the product
+// library): lane 0 of every wavefront stores the 100 MHz constant clock at numbered points.
+#ifdef TETRI_TRACE
+constexpr int kTraceMarks = 8, kTraceWaves = 8, kTraceBlocks = 4096;
+static __device__ unsigned long long g_trace[kTraceBlocks * kTraceWaves * kTraceMarks];
+static __device__ unsigned long long g_trace2[kTraceBlocks * kTraceWaves * 8];
+#define TETRI_MARK(i_)                                                                                  \
+    do {                                                                                                \
+        if ((threadIdx.x & 63) == 0 && blockIdx.x < tetri_dev::kTraceBlocks)                            \
+            tetri_dev::g_trace[(blockIdx.x * tetri_dev::kTraceWaves + (threadIdx.x >> 6)) * tetri_dev::kTraceMarks + (i_)] = \
+                __builtin_amdgcn_s_memrealtime();                                                       \
+    } while (0)
+// Phase clocks inside the main loop: TETRI_T(i) samples the shader clock into tt[i] without
+// waiting for it; TETRI_ACC adds the differences of a block's samples to per-phase sums, which
+// TETRI_ACC_OUT stores behind the marks.
+#define TETRI_T_DECL uint32_t tt[6] = {0, 0, 0, 0, 0, 0}, tacc[6] = {0, 0, 0, 0, 0, 0}
+#define TETRI_T(i_) tt[i_] = (uint32_t)__builtin_readcyclecounter()
+#define TETRI_TSET(a_, b_) tt[a_] = tt[b_]
+#define TETRI_ACC(i_, a_, b_) tacc[i_] += tt[b_] - tt[a_]
+#define TETRI_COUNT(i_) tacc[i_] += 1
+#define TETRI_ACC_OUT                                                                                   \
+    do {                                                                                                \
+        if ((threadIdx.x & 63) == 0 && blockIdx.x < tetri_dev::kTraceBlocks)                            \
+            for (int i_ = 0; i_ < 6; ++i_)                                                              \
+                tetri_dev::g_trace2[(blockIdx.x * tetri_dev::kTraceWaves + (threadIdx.x >> 6)) * 8 + i_] = tacc[i_]; \
+    } while (0)
+#else
+#define TETRI_MARK(i_) do { } while (0)
+#define TETRI_T_DECL do { } while (0)
+#define TETRI_T(i_) do { } while (0)
+#define TETRI_TSET(a_, b_) do { } while (0)
+#define TETRI_ACC(i_, a_, b_) do { } while (0)
+#define TETRI_COUNT(i_) do { } while (0)
+#define TETRI_ACC_OUT do { } while (0)
+#endif
+
 // A row of zeros: out-of-range key rows of a partial tile are loaded from here.
 static __device__ __attribute__((aligned(256))) uint4 g_zero_row[16];
 
-template <int D> __device__ __forceinline__ int k_swizzle(int row)
+template <int D> __host__ __device__ __forceinline__ constexpr int k_swizzle(int row)
 {
     // 16 consecutive rows must land in 16 different 16-byte bank groups
     return (D == 128) ? (row & 15) : ((row >> 1) & 7);
 }
-template <int D> __device__ __forceinline__ int v_swizzle(int row)
+template <int D> __host__ __device__ __forceinline__ constexpr int v_swizzle(int row)
 {
     // 4 consecutive rows x 64 contiguous bytes must land in 4 different 64-byte bank groups
     return (D == 128) ? ((row & 3) << 2) : (((row ^ (row >> 1)) & 1) << 2);
@@ -71,6 +108,29 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
 __device__ __forceinline__ void dma16_sbase(const void *sbase, uint32_t voff, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+// A group of such loads that share one scalar base and one LDS base: instruction i moves
+// 16 bytes per lane from sbase + voff_i + 1024*i to LDS byte lds_base + 1024*i + 16*lane.  The
+// instruction's immediate offset advances the global and the LDS address alike, so M0 is written
+// once per group.
+__device__ __forceinline__ void dma16_group4(const void *sbase, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %4\n\t"
+                 "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:3072" ::"v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ void dma16_group2(const void *sbase, uint32_t v0, uint32_t v1, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %2\n\t"
+                 "global_load_lds_dwordx4 %1, %2 offset:1024" ::"v"(v0), "v"(v1), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+// One load of such a group on its own (IMM = 1024 * i).
+template <int IMM> __device__ __forceinline__ void dma16_imm(const void *sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(IMM) : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {

@@ -61,56 +61,90 @@ __device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane, 
     lo.v_new = r0 * new_row_bytes + vc * 16;
 }
 // XOR that turns instruction 0's chunk into instruction i's (in bytes).
-template <int D> __device__ __forceinline__ constexpr uint32_t k_inst_xor(int i)
+template <int D> __host__ __device__ __forceinline__ constexpr uint32_t k_inst_xor(int i)
 {
     return (uint32_t)(k_swizzle<D>((64 / (D / 8)) * i) * 16);
 }
-template <int D> __device__ __forceinline__ constexpr uint32_t v_inst_xor(int i)
+template <int D> __host__ __device__ __forceinline__ constexpr uint32_t v_inst_xor(int i)
 {
     return (uint32_t)(v_swizzle<D>((64 / (D / 8)) * i) * 16);
 }
 
-// Issue the direct-to-LDS loads of this wavefront's 16 rows of stage `it` (K and V).
+// Wave-uniform pieces of a wavefront's load addresses, fixed for the whole kernel.
+struct WaveSrc {
+    const char *pool_k;         // K block of kv head kh in page 0 of the pool
+    uint32_t page_bytes;        // one page: K and V blocks of every kv head
+    uint32_t v_delta;           // from a page's K block to its V block of the same head
+    const char *new_k, *new_v;  // row 16*wave of the segment, kv head kh, in k_new / v_new
+    uint32_t stage_new_bytes;   // a stage's worth of rows in k_new / v_new
+};
+
+// The direct-to-LDS loads of this wavefront's 16 rows of one stage (K and V): one scalar base per
+// matrix; the NI instructions of a matrix differ only in their per-lane offsets.
+struct StageLoads {
+    const char *kb, *vb;        // row j0 of the stage part, K and V
+    uint32_t step;              // bytes the rows of two instructions are further apart than 1 KB
+    uint32_t kdst;              // LDS byte address of the K rows; the V rows are 2 * STAGE_BYTES further
+    int j0, limit;              // first key row, and the end of the key range it belongs to
+    bool ctx;                   // pool rows (else rows of k_new / v_new)
+    uint32_t ko, vo;            // per-lane byte offsets of the first instruction's rows, K and V
+};
+
+// Where stage `it` comes from.  Returns whether all 16 rows exist.
 template <int D, int KS>
-__device__ __forceinline__ void issue_stage_loads(const KeySource &ks, const LaneOffsets<D> &lo, int page, int it,
-                                                  int wave, int lane, int new_row_bytes, uint32_t k_lds, uint32_t v_lds)
+__device__ __forceinline__ bool describe_stage_loads(const KeySource &ks, const WaveSrc &ws, const LaneOffsets<D> &lo, int page, int it,
+                                                     int wave, int new_row_bytes, uint32_t k_lds, StageLoads &sl)
+{
+    constexpr int RPI = 64 / (D / 8);
+    constexpr int STAGE = kBNW * KS;
+    sl.ctx = it < ks.n_ctx_tiles;
+    const int jn = it - ks.n_ctx_tiles;
+    sl.j0 = (sl.ctx ? it : jn) * STAGE + 16 * wave;
+    sl.limit = sl.ctx ? ks.L : ks.n_new;
+    sl.kdst = k_lds + wave * (16 * D * 2);
+    sl.ko = sl.ctx ? lo.k_ctx : lo.k_new;
+    sl.vo = sl.ctx ? lo.v_ctx : lo.v_new;
+    // pool rows of an instruction follow the previous one's directly (the immediate offset covers
+    // it); rows of k_new / v_new are `step` bytes further apart than that
+    if (sl.ctx) {
+        sl.kb = ws.pool_k + (size_t)page * ws.page_bytes;
+        sl.vb = sl.kb + ws.v_delta;
+        sl.step = 0;
+    } else {
+        const size_t off = (size_t)jn * ws.stage_new_bytes;
+        sl.kb = ws.new_k + off;
+        sl.vb = ws.new_v + off;
+        sl.step = RPI * new_row_bytes - 1024;
+    }
+    return sl.j0 + 16 <= sl.limit;
+}
+
+// All loads of a stage at once.
+template <int D, int KS>
+__device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool full, int lane)
 {
     constexpr int CH = D / 8, RPI = 64 / CH, NI = 16 / RPI;
-    constexpr int STAGE = kBNW * KS;
-    const bool is_ctx = it < ks.n_ctx_tiles;
-    const int base = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE;
-    const int limit = is_ctx ? ks.L : ks.n_new;
-    const int j0 = base + 16 * wave;                             // first key row of this wavefront
-    const uint32_t kdst = k_lds + wave * (16 * D * 2), vdst = v_lds + wave * (16 * D * 2);
-    // wave-uniform base addresses of row j0 and the distance between row groups of two instructions
-    const char *kb, *vb;
-    int inst_bytes;
-    if (is_ctx) {
-        kb = reinterpret_cast<const char *>(ks.pages) + ((size_t)page * 2 * ks.Hkv + ks.kh) * (size_t)(kPage * D * 2);
-        vb = kb + (size_t)ks.Hkv * (kPage * D * 2);
-        inst_bytes = RPI * D * 2;
-    } else {
-        const size_t off = ((size_t)(ks.row_base + j0) * ks.Hkv + ks.kh) * (size_t)(D * 2);
-        kb = reinterpret_cast<const char *>(ks.k_new) + off;
-        vb = reinterpret_cast<const char *>(ks.v_new) + off;
-        inst_bytes = RPI * new_row_bytes;
-    }
-    const uint32_t ko = is_ctx ? lo.k_ctx : lo.k_new, vo = is_ctx ? lo.v_ctx : lo.v_new;
-    if (j0 + 16 <= limit) {
-        // all 16 rows exist: scalar base + per-lane offset
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            dma16_sbase(kb + (size_t)i * inst_bytes, ko ^ k_inst_xor<D>(i), kdst + 1024 * i);
-            dma16_sbase(vb + (size_t)i * inst_bytes, vo ^ v_inst_xor<D>(i), vdst + 1024 * i);
+    constexpr uint32_t V_LDS = 2 * (kBNW * KS) * D * 2;
+    static_assert(RPI * D * 2 == 1024 && (NI == 4 || NI == 2), "one instruction moves 1 KB");
+    const uint32_t ko = sl.ko, vo = sl.vo, step = sl.step;
+    const uint32_t kdst = sl.kdst, vdst = sl.kdst + V_LDS;
+    if (full) {
+        if constexpr (NI == 4) {
+            dma16_group4(sl.kb, ko, (ko ^ k_inst_xor<D>(1)) + step, (ko ^ k_inst_xor<D>(2)) + 2 * step, (ko ^ k_inst_xor<D>(3)) + 3 * step, kdst);
+            dma16_group4(sl.vb, vo, (vo ^ v_inst_xor<D>(1)) + step, (vo ^ v_inst_xor<D>(2)) + 2 * step, (vo ^ v_inst_xor<D>(3)) + 3 * step, vdst);
+        } else {
+            dma16_group2(sl.kb, ko, (ko ^ k_inst_xor<D>(1)) + step, kdst);
+            dma16_group2(sl.vb, vo, (vo ^ v_inst_xor<D>(1)) + step, vdst);
         }
     } else {
         // ragged end of the key range: rows past the limit come from a row of zeros
         const char *zero = reinterpret_cast<const char *>(g_zero_row);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const bool ok = j0 + RPI * i + lane / CH < limit;
-            dma16(ok ? kb + (size_t)i * inst_bytes + (ko ^ k_inst_xor<D>(i)) : zero, kdst + 1024 * i);
-            dma16(ok ? vb + (size_t)i * inst_bytes + (vo ^ v_inst_xor<D>(i)) : zero, vdst + 1024 * i);
+            const bool ok = sl.j0 + RPI * i + lane / CH < sl.limit;
+            const size_t inst = (size_t)i * (step + 1024);
+            dma16(ok ? sl.kb + inst + (ko ^ k_inst_xor<D>(i)) : zero, kdst + 1024 * i);
+            dma16(ok ? sl.vb + inst + (vo ^ v_inst_xor<D>(i)) : zero, vdst + 1024 * i);
         }
     }
 }
@@ -169,6 +203,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int half = lane >> 5, l32 = lane & 31;
     const int BM = 32 * p.rb;
     const int S = p.S;
+    TETRI_MARK(0);
 
     // ---- workgroups past the attention grid copy the chunk's new K/V rows into their page slots
     // (fused KV append; they land on CUs the attention grid leaves idle or finish in its tail)
@@ -186,11 +221,16 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
 
     // ---- which (segment, row tile) is it?  Tiles never span two segments.  64 segments are
     // examined at a time: lane l takes segment s0 + l, a wave-wide prefix sum of the tile counts
-    // finds the segment that owns `tile`.
-    int s = -1, t0 = -1, seg_cu = 0, n_s = 0;
+    // finds the segment that owns `tile`.  The lane also fetches what the owner will need next
+    // (context length, the page of this wavefront's first rows), so that the kernel's first loads
+    // of K and V are one memory round trip away from its start, not three.
+    int s = -1, t0 = -1, seg_cu = 0, n_s = 0, L = 0, page = 0;
+    const int first_page = min(wave, p.max_blocks - 1);
     for (int s0 = 0; s0 < S; s0 += 64) {
         const int idx = s0 + lane;
         const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
+        const int ctx_len = idx < S ? p.ctx[idx] : 0;
+        const int pg = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page] : 0;
         const int nt = (b - a + BM - 1) / BM;          // 0 for lanes past the last segment
         int incl = nt;
 #pragma unroll
@@ -205,6 +245,8 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             t0 = (tile - __builtin_amdgcn_readlane(incl - nt, src)) * BM;
             seg_cu = __builtin_amdgcn_readlane(a, src);
             n_s = __builtin_amdgcn_readlane(b - a, src);
+            L = __builtin_amdgcn_readlane(ctx_len, src);
+            page = __builtin_amdgcn_readlane(pg, src);
             break;
         }
         tile -= __builtin_amdgcn_readlane(incl, 63);
@@ -222,7 +264,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         }
         return;
     }
-    const int L = ((const const_i32 *)(uintptr_t)p.ctx)[s];
+    TETRI_MARK(1);
     KeySource ks;
     ks.pages = p.pages; ks.k_new = p.k_new; ks.v_new = p.v_new;
     ks.bt_row = p.bt + (size_t)s * p.max_blocks;
@@ -237,29 +279,47 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const bool row_ok = t < n_s;
     const bool wave_has_rows = tw0 < n_s;
 
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7]
+    bf16x8 qf[KSTEPS];
+    {
+        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(seg_cu + (row_ok ? t : 0)) * p.Hq + head) * D);
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) {
+            const uint4 v = row_ok ? qp[2 * st + half] : make_uint4(0, 0, 0, 0);
+            qf[st] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
     const int new_row_bytes = p.Hkv * D * 2;
     LaneOffsets<D> lo;
     init_lane_offsets<D>(lo, lane, new_row_bytes);
     const uint32_t smem_lds = lds_address(smem);
     constexpr uint32_t STAGE_BYTES = STAGE_U4 * 16;   // bytes of one matrix of one stage
 
-    int page = load_stage_page<KS>(ks, 0, wave);
-    issue_stage_loads<D, KS>(ks, lo, page, 0, wave, lane, new_row_bytes, smem_lds, smem_lds + 2 * STAGE_BYTES);
-    page = load_stage_page<KS>(ks, 1, wave);
-
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7]
-    bf16x8 qf[KSTEPS];
+    WaveSrc ws;
+    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)ks.kh * (kPage * D * 2);
+    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
+    ws.v_delta = p.Hkv * (kPage * D * 2);
     {
-        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(ks.row_base + (row_ok ? t : 0)) * p.Hq + head) * D);
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) {
-            uint4 v = row_ok ? qp[2 * st + half] : make_uint4(0, 0, 0, 0);
-            if (p.neg) {         // a negative scale is applied as |scale| to -q (exact in bf16)
-                v.x ^= 0x80008000u; v.y ^= 0x80008000u; v.z ^= 0x80008000u; v.w ^= 0x80008000u;
-            }
-            qf[st] = __builtin_bit_cast(bf16x8, v);
-        }
+        const size_t off = ((size_t)(ks.row_base + 16 * wave) * p.Hkv + ks.kh) * (size_t)(D * 2);
+        ws.new_k = reinterpret_cast<const char *>(p.k_new) + off;
+        ws.new_v = reinterpret_cast<const char *>(p.v_new) + off;
     }
+    ws.stage_new_bytes = STAGE * new_row_bytes;
+    static_assert(kBNW * KS / kPage == kSlots * KS, "stage 0: wavefront w loads page w of the segment");
+    StageLoads sl;
+    {
+        const bool full = describe_stage_loads<D, KS>(ks, ws, lo, page, 0, wave, new_row_bytes, smem_lds, sl);
+        issue_stage_loads<D, KS>(sl, full, lane);
+    }
+    // The loads of the next stage are not issued by all wavefronts at once right after the barrier:
+    // the load unit takes a wavefront's 8 KB in about 128 cycles and a wavefront that finds it busy
+    // stalls in front of its own matrix instructions.  Each wavefront has one of four points in
+    // the instruction stream between two barriers at which it issues its loads (the two wavefronts
+    // of a SIMD use different ones), so that at any time most wavefronts are computing.
+    bool pend = false;                               // the next stage's loads are described in sl, not issued
+    const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
+    page = load_stage_page<KS>(ks, 1, wave);
 
     f32x16 o[DBLK];
 #pragma unroll
@@ -268,7 +328,10 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
     float m = -1e30f;        // running row max (in units of log2: score * c)
     float lsum = 0.f;        // this lane's share of the running row sum
-    const float c = p.c;
+    // scores are multiplied by c = scale * log2(e), of either sign; a masked score is the infinity
+    // that c turns into -inf
+    const float c = p.neg ? -p.c : p.c;
+    const float masked = p.neg ? INFINITY : -INFINITY;
     const int blk = lane >> 4, i16 = lane & 15;
 
     // Fragment loads from LDS.  K: lane holds key (row) l32 of a 32-key block, d = 16*st + 8*half .. +7
@@ -326,12 +389,30 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // Make stage `it` the current one: its loads have landed for every wavefront, nobody reads the
     // other buffer any more, so the loads of stage it+1 can go there.  `page` always belongs to
     // the stage whose loads are issued next; it is fetched one stage ahead.
-    auto enter_stage = [&](int it) {
+    // Entering a stage has two halves: the wait, after which the wavefront may read the stage (it
+    // requests its first K fragments from LDS right away), and handing out the next stage's loads.
+    // `pv_before`: a PV product is pending, i.e. deferred loads will meet their issue point before
+    // the next stage is entered.
+    auto issue_pending = [&](int point) {
+        if (pend && load_point == point) {
+            issue_stage_loads<D, KS>(sl, true, lane);
+            pend = false;
+        }
+    };
+    auto sync_stage = [&](int it) -> int {
+        if (pend) {                                    // rare: the stage had too few blocks to reach the point
+            issue_stage_loads<D, KS>(sl, true, lane);
+            pend = false;
+        }
         wait_vm<0>();
         __syncthreads();
+        return stage_blocks(it);
+    };
+    auto next_stage_loads = [&](int it, int nb, bool pv_before) {
         if (it + 1 < n_stages) {
-            const uint32_t nb = smem_lds + ((it + 1) & 1) * STAGE_BYTES;
-            issue_stage_loads<D, KS>(ks, lo, page, it + 1, wave, lane, new_row_bytes, nb, nb + 2 * STAGE_BYTES);
+            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + ((it + 1) & 1) * STAGE_BYTES, sl);
+            if (full && pv_before && nb != 0 && load_point != 0) pend = true;
+            else issue_stage_loads<D, KS>(sl, full, lane);
         }
         page = load_stage_page<KS>(ks, it + 2, wave);
     };
@@ -350,16 +431,19 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // Every wavefront enters every stage exactly once (one barrier each), whether or not it has
     // blocks there.
     int it = 0;
-    enter_stage(0);
-    int nblk = stage_blocks(0);
-    while (nblk == 0 && ++it < n_stages) {
-        enter_stage(it);
-        nblk = stage_blocks(it);
+    TETRI_MARK(2);
+    TETRI_T_DECL;
+    int nblk = sync_stage(0);
+    TETRI_MARK(3);
+    while (nblk == 0 && it + 1 < n_stages) {
+        next_stage_loads(it, 0, false);
+        nblk = sync_stage(++it);
     }
-    if (it < n_stages) {
+    if (nblk != 0) {
         int kb = 0;
         bf16x8 kf[KSTEPS];
         load_k(kf, (it & 1) * STAGE_BYTES);
+        next_stage_loads(it, nblk, false);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
         // weights of a block from its scores and the row's reference exponent m: bf16-rounded, laid out
@@ -383,6 +467,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         // exponentiating and rounding this block's weights on the VALU against the reference exponent
         // m the row already has; then the PV product with the V fragments in vf.
         auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, const s16x8 (&vf)[2 * DBLK]) {
+            TETRI_T(3);
             __builtin_amdgcn_sched_barrier(0);
             s_next = qk(kf);
             bf16x8 pf[2];
@@ -394,16 +479,18 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+            TETRI_T(4);
+            issue_pending(1);
             // m is only a reference point, not the exact row maximum: any value keeps the result exact
             // as long as the weights stay in range.  Only when a lane's weights of this block sum to
             // more than 2^16 (or overflowed: first block, or scores far above anything seen before) is
             // m raised to the true maximum, O and the row sum rescaled in place, and the weights
             // recomputed.  The two half-waves of a row take the same decision.
             if (__builtin_amdgcn_ballot_w64(!(l_blk <= 65536.0f)) != 0) {
-                float mx = s_cur[0];
+                float mx = s_cur[0] * c;
 #pragma unroll
-                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
-                mx = half_swap_max(mx) * c;
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v] * c);
+                mx = half_swap_max(mx);
                 const float m_new = fmaxf(m, mx);
                 float alpha = __builtin_amdgcn_exp2f(m - m_new);
                 // the wait state a transcendental result needs before a VALU use; the compiler does not
@@ -418,12 +505,20 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 l_blk = weights(s_cur, pf);
             }
             lsum += l_blk;
-            // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7
+            // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7.
+#ifdef EXP_PRIO
+            __builtin_amdgcn_s_setprio(EXP_PRIO);
+#endif
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
+                if (j == 0) issue_pending(2);
+            }
+#ifdef EXP_PRIO
+            __builtin_amdgcn_s_setprio(0);
+#endif
         };
         // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
         // after the last block.
@@ -434,32 +529,47 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
             // V fragments of this block: in registers before the stage may be left
             s16x8 vf[2 * DBLK];
+            TETRI_T(0);
+            TETRI_TSET(1, 0);
+            TETRI_TSET(2, 0);
             load_v(vf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
             // ---- the block after this one
-            bool have_next = true;
+            bool have_next = true, entered = false;
             if (kb + 1 < nblk) {
                 ++kb;
             } else {
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS
+                TETRI_T(1);
+                TETRI_TSET(2, 1);
                 kb = 0;
                 nblk = 0;
-                while (nblk == 0 && ++it < n_stages) {
-                    enter_stage(it);
-                    nblk = stage_blocks(it);
+                while (nblk == 0 && it + 1 < n_stages) {
+                    nblk = sync_stage(++it);
+                    TETRI_T(2);
+                    if (nblk == 0) next_stage_loads(it, 0, true);
                 }
-                have_next = it < n_stages;
+                have_next = entered = nblk != 0;
             }
             if (have_next) load_k(kf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
+            if (entered) next_stage_loads(it, nblk, true);
+            else issue_pending(3);
             // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
             // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
             if (need_mask) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
-                    if (key > bound) s_cur[v] = -INFINITY;
+                    if (key > bound) s_cur[v] = masked;
                 }
             }
             softmax_pv(s_cur, s_next, vf);
+            TETRI_T(5);
+            TETRI_ACC(0, 0, 1);     // V reads issued + (stage end) wait for them
+            TETRI_ACC(1, 1, 2);     // loads landed + barrier
+            TETRI_ACC(2, 2, 3);     // K reads issued, next loads, mask
+            TETRI_ACC(3, 3, 4);     // wait for K, QK + softmax
+            TETRI_ACC(4, 4, 5);     // check, wait for V, PV
+            TETRI_COUNT(5);
             return have_next;
         };
         f32x16 s_a = qk(kf), s_b;
@@ -469,33 +579,61 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         }
     }
 
-    // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes
+    TETRI_MARK(4);
+    TETRI_ACC_OUT;
+    // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes.
+    // The partial O goes into the stage buffer that held the stage before the last one: nobody reads
+    // it any more once every wavefront has entered the last stage, so no barrier is needed before
+    // writing.  Its K region takes slots 0 and 1, its V region slots 2 and 3; lane l's four
+    // consecutive accumulator elements are one 16-byte unit.
     float ltot = half_swap_sum(lsum);
+    float w0 = 1.f;
     if constexpr (KS == 2) {
-        __syncthreads();                    // all stage buffers are dead now
-        float *part = reinterpret_cast<float *>(smem) + slot * (DBLK * 16 * 64);
+        static_assert(2 * (DBLK * 16 * 64 * 4) == STAGE_BYTES, "two slots per matrix region");
+        char *dead = reinterpret_cast<char *>(smem) + (n_stages & 1) * STAGE_BYTES + (slot >> 1) * (2 * STAGE_BYTES);
+        f32x4 *part = reinterpret_cast<f32x4 *>(dead + (slot & 1) * (DBLK * 16 * 64 * 4));
         if (kq == 1) {
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) part[(db * 16 + v) * 64 + lane] = o[db][v];
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
+                    part[(db * 4 + q4) * 64 + lane] = x;
+                }
             if (half == 0) { Mstat[slot][0][l32] = m; Mstat[slot][1][l32] = ltot; }
         }
         __syncthreads();
+        TETRI_MARK(5);
         if (kq == 1) return;
         const float m1 = Mstat[slot][0][l32], l1 = Mstat[slot][1][l32];
         const float mstar = fmaxf(m, m1);
-        const float w0 = __builtin_amdgcn_exp2f(m - mstar), w1 = __builtin_amdgcn_exp2f(m1 - mstar);
+        w0 = __builtin_amdgcn_exp2f(m - mstar);
+        float w1 = __builtin_amdgcn_exp2f(m1 - mstar);
         ltot = ltot * w0 + l1 * w1;
+        const float inv = __builtin_amdgcn_rcpf(ltot);
+        w0 *= inv;
+        w1 *= inv;
+        if (!row_ok) return;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] = o[db][v] * w0 + part[(db * 16 + v) * 64 + lane] * w1;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 x = part[(db * 4 + q4) * 64 + lane];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[db][q4 * 4 + e] = o[db][q4 * 4 + e] * w0 + x[e] * w1;
+            }
+    } else {
+        if (!row_ok) return;
+        w0 = __builtin_amdgcn_rcpf(ltot);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= w0;
     }
 
-    // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
-    if (!row_ok) return;
-    const float inv = __builtin_amdgcn_rcpf(ltot);
+    // ---- store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
     uint16_t *orow = p.out + ((size_t)(ks.row_base + t) * p.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
@@ -503,9 +641,10 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         for (int q4 = 0; q4 < 4; ++q4) {
             bf16x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)o[db][q4 * 4 + e];
             *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
         }
+    TETRI_MARK(6);
 }
 
 template <int D, int KS>
@@ -516,6 +655,20 @@ hipError_t launch(const AttnParams &p, hipStream_t stream)
 }
 
 }  // namespace
+
+#ifdef TETRI_TRACE
+// Copies the timeline marks of the last launches to the host (trace builds only).
+extern "C" TETRI_API int tetri_debug_trace(unsigned long long *host, size_t count)
+{
+    const size_t all = (size_t)kTraceBlocks * kTraceWaves * kTraceMarks;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * (count < all ? count : all));
+}
+extern "C" TETRI_API int tetri_debug_phases(unsigned long long *host, size_t count)
+{
+    const size_t all = (size_t)kTraceBlocks * kTraceWaves * 8;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace2), sizeof(unsigned long long) * (count < all ? count : all));
+}
+#endif
 
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream)
 {

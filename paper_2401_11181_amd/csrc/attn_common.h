@@ -23,35 +23,14 @@ constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round
 #ifdef TETRI_TRACE
 constexpr int kTraceMarks = 8, kTraceWaves = 8, kTraceBlocks = 4096;
 static __device__ unsigned long long g_trace[kTraceBlocks * kTraceWaves * kTraceMarks];
-static __device__ unsigned long long g_trace2[kTraceBlocks * kTraceWaves * 8];
 #define TETRI_MARK(i_)                                                                                  \
     do {                                                                                                \
         if ((threadIdx.x & 63) == 0 && blockIdx.x < tetri_dev::kTraceBlocks)                            \
             tetri_dev::g_trace[(blockIdx.x * tetri_dev::kTraceWaves + (threadIdx.x >> 6)) * tetri_dev::kTraceMarks + (i_)] = \
                 __builtin_amdgcn_s_memrealtime();                                                       \
     } while (0)
-// Phase clocks inside the main loop: TETRI_T(i) samples the shader clock into tt[i] without
-// waiting for it; TETRI_ACC adds the differences of a block's samples to per-phase sums, which
-// TETRI_ACC_OUT stores behind the marks.
-#define TETRI_T_DECL uint32_t tt[6] = {0, 0, 0, 0, 0, 0}, tacc[6] = {0, 0, 0, 0, 0, 0}
-#define TETRI_T(i_) tt[i_] = (uint32_t)__builtin_readcyclecounter()
-#define TETRI_TSET(a_, b_) tt[a_] = tt[b_]
-#define TETRI_ACC(i_, a_, b_) tacc[i_] += tt[b_] - tt[a_]
-#define TETRI_COUNT(i_) tacc[i_] += 1
-#define TETRI_ACC_OUT                                                                                   \
-    do {                                                                                                \
-        if ((threadIdx.x & 63) == 0 && blockIdx.x < tetri_dev::kTraceBlocks)                            \
-            for (int i_ = 0; i_ < 6; ++i_)                                                              \
-                tetri_dev::g_trace2[(blockIdx.x * tetri_dev::kTraceWaves + (threadIdx.x >> 6)) * 8 + i_] = tacc[i_]; \
-    } while (0)
 #else
 #define TETRI_MARK(i_) do { } while (0)
-#define TETRI_T_DECL do { } while (0)
-#define TETRI_T(i_) do { } while (0)
-#define TETRI_TSET(a_, b_) do { } while (0)
-#define TETRI_ACC(i_, a_, b_) do { } while (0)
-#define TETRI_COUNT(i_) do { } while (0)
-#define TETRI_ACC_OUT do { } while (0)
 #endif
 
 // A row of zeros: out-of-range key rows of a partial tile are loaded from here.
@@ -66,6 +45,13 @@ template <int D> __host__ __device__ __forceinline__ constexpr int v_swizzle(int
 {
     // 4 consecutive rows x 64 contiguous bytes must land in 4 different 64-byte bank groups
     return (D == 128) ? ((row & 3) << 2) : (((row ^ (row >> 1)) & 1) << 2);
+}
+
+// n / d for a divisor fixed at launch: magic = ceil(2^32 / d), or 0 for d = 1.  Exact while
+// n * d < 2^32 (the host checks the launch's largest n).
+__device__ __forceinline__ int magic_div(int n, uint32_t magic)
+{
+    return magic != 0 ? (int)__umulhi((uint32_t)n, magic) : n;
 }
 
 // Exchange between the two half-waves (lanes l and l^32 hold the same query) with

@@ -75,8 +75,9 @@ struct WaveSrc {
     const char *pool_k;         // K block of kv head kh in page 0 of the pool
     uint32_t page_bytes;        // one page: K and V blocks of every kv head
     uint32_t v_delta;           // from a page's K block to its V block of the same head
-    const char *new_k, *new_v;  // row 16*wave of the segment, kv head kh, in k_new / v_new
+    const char *new_k, *new_v;  // first row of the segment, kv head kh, in k_new / v_new
     uint32_t stage_new_bytes;   // a stage's worth of rows in k_new / v_new
+    uint32_t wave_new_bytes;    // a wavefront's 16 rows
 };
 
 // The direct-to-LDS loads of this wavefront's 16 rows of one stage (K and V): one scalar base per
@@ -111,7 +112,7 @@ __device__ __forceinline__ bool describe_stage_loads(const KeySource &ks, const 
         sl.vb = sl.kb + ws.v_delta;
         sl.step = 0;
     } else {
-        const size_t off = (size_t)jn * ws.stage_new_bytes;
+        const size_t off = (size_t)jn * ws.stage_new_bytes + (size_t)wave * ws.wave_new_bytes;
         sl.kb = ws.new_k + off;
         sl.vb = ws.new_v + off;
         sl.step = RPI * new_row_bytes - 1024;
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = wave % kSlots, kq = wave / kSlots;    // row/head slot, key part
     const int half = lane >> 5, l32 = lane & 31;
-    const int BM = 32 * p.rb;
+    const int BM = 32 << p.rb_shift;
     const int S = p.S;
     TETRI_MARK(0);
 
@@ -214,24 +215,24 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // ---- workgroup id -> (head group, row tile); a head group's tiles share one XCD
     const int per_xcd = p.attn_grid / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
-    const int groups = p.Hq / p.hpw;
-    if (logical >= p.tiles * groups) return;
-    const int grp = logical / p.tiles;
-    int tile = p.tiles - 1 - logical % p.tiles;        // late (long) tiles first
+    if (logical >= p.tiles * p.groups) return;
+    const int grp = magic_div(logical, p.tiles_magic);
+    int tile = p.tiles - 1 - (logical - grp * p.tiles);    // late (long) tiles first
 
     // ---- which (segment, row tile) is it?  Tiles never span two segments.  64 segments are
     // examined at a time: lane l takes segment s0 + l, a wave-wide prefix sum of the tile counts
     // finds the segment that owns `tile`.  The lane also fetches what the owner will need next
     // (context length, the page of this wavefront's first rows), so that the kernel's first loads
     // of K and V are one memory round trip away from its start, not three.
-    int s = -1, t0 = -1, seg_cu = 0, n_s = 0, L = 0, page = 0;
-    const int first_page = min(wave, p.max_blocks - 1);
+    int s = -1, t0 = -1, seg_cu = 0, n_s = 0, L = 0, page = 0, page_hi = 0;
+    const int first_page = min(wave, p.max_blocks - 1), first_page_hi = min(wave + kSlots, p.max_blocks - 1);
     for (int s0 = 0; s0 < S; s0 += 64) {
         const int idx = s0 + lane;
         const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
         const int ctx_len = idx < S ? p.ctx[idx] : 0;
         const int pg = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page] : 0;
-        const int nt = (b - a + BM - 1) / BM;          // 0 for lanes past the last segment
+        const int pg_hi = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page_hi] : 0;
+        const int nt = (b - a + BM - 1) >> (5 + p.rb_shift);   // 0 for lanes past the last segment
         int incl = nt;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -247,11 +248,12 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             n_s = __builtin_amdgcn_readlane(b - a, src);
             L = __builtin_amdgcn_readlane(ctx_len, src);
             page = __builtin_amdgcn_readlane(pg, src);
+            page_hi = __builtin_amdgcn_readlane(pg_hi, src);
             break;
         }
         tile -= __builtin_amdgcn_readlane(incl, 63);
     }
-    const int hh = slot % p.hpw, rbk = slot / p.hpw;
+    const int hh = slot & (p.hpw - 1), rbk = slot >> p.hpw_shift;
     const int head = grp * p.hpw + hh;
     if (t0 < 0) {
         // padding rows [cu[S], C): written as +0
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     KeySource ks;
     ks.pages = p.pages; ks.k_new = p.k_new; ks.v_new = p.v_new;
     ks.bt_row = p.bt + (size_t)s * p.max_blocks;
-    ks.Hkv = p.Hkv; ks.kh = (grp * p.hpw) / p.g; ks.row_base = seg_cu; ks.L = L;
+    ks.Hkv = p.Hkv; ks.kh = magic_div(grp, p.kv_magic); ks.row_base = seg_cu; ks.L = L;
     ks.n_new = min(n_s, t0 + BM);                      // new keys any row of this tile may see
     ks.n_ctx_tiles = (L + STAGE - 1) / STAGE;
     ks.max_blocks = p.max_blocks;
@@ -278,17 +280,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int t = tw0 + l32;               // local row of this lane's query
     const bool row_ok = t < n_s;
     const bool wave_has_rows = tw0 < n_s;
-
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7]
-    bf16x8 qf[KSTEPS];
-    {
-        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(seg_cu + (row_ok ? t : 0)) * p.Hq + head) * D);
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) {
-            const uint4 v = row_ok ? qp[2 * st + half] : make_uint4(0, 0, 0, 0);
-            qf[st] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
 
     const int new_row_bytes = p.Hkv * D * 2;
     LaneOffsets<D> lo;
@@ -301,16 +292,22 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
     ws.v_delta = p.Hkv * (kPage * D * 2);
     {
-        const size_t off = ((size_t)(ks.row_base + 16 * wave) * p.Hkv + ks.kh) * (size_t)(D * 2);
+        const size_t off = ((size_t)ks.row_base * p.Hkv + ks.kh) * (size_t)(D * 2);
         ws.new_k = reinterpret_cast<const char *>(p.k_new) + off;
         ws.new_v = reinterpret_cast<const char *>(p.v_new) + off;
     }
     ws.stage_new_bytes = STAGE * new_row_bytes;
+    ws.wave_new_bytes = 16 * new_row_bytes;
     static_assert(kBNW * KS / kPage == kSlots * KS, "stage 0: wavefront w loads page w of the segment");
+    // Stage 0: the wavefronts of key part 0 reach this point first (the older wavefront of a SIMD
+    // is served first), so they issue the loads of their partner in part 1 as well.
     StageLoads sl;
-    {
-        const bool full = describe_stage_loads<D, KS>(ks, ws, lo, page, 0, wave, new_row_bytes, smem_lds, sl);
-        issue_stage_loads<D, KS>(sl, full, lane);
+    if (kq == 0) {
+#pragma unroll
+        for (int part = 0; part < KS; ++part) {
+            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, part == 0 ? page : page_hi, 0, wave + part * kSlots, new_row_bytes, smem_lds, sl);
+            issue_stage_loads<D, KS>(sl, full, lane);
+        }
     }
     // The loads of the next stage are not issued by all wavefronts at once right after the barrier:
     // the load unit takes a wavefront's 8 KB in about 128 cycles and a wavefront that finds it busy
@@ -320,6 +317,15 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     bool pend = false;                               // the next stage's loads are described in sl, not issued
     const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
     page = load_stage_page<KS>(ks, 1, wave);
+
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7].  Lanes
+    // past the segment's last row read its first row instead: their results are never stored.
+    bf16x8 qf[KSTEPS];
+    {
+        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(seg_cu + (row_ok ? t : 0)) * p.Hq + head) * D);
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) qf[st] = __builtin_bit_cast(bf16x8, qp[2 * st + half]);
+    }
 
     f32x16 o[DBLK];
 #pragma unroll
@@ -432,7 +438,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // blocks there.
     int it = 0;
     TETRI_MARK(2);
-    TETRI_T_DECL;
     int nblk = sync_stage(0);
     TETRI_MARK(3);
     while (nblk == 0 && it + 1 < n_stages) {
@@ -467,7 +472,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         // exponentiating and rounding this block's weights on the VALU against the reference exponent
         // m the row already has; then the PV product with the V fragments in vf.
         auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, const s16x8 (&vf)[2 * DBLK]) {
-            TETRI_T(3);
             __builtin_amdgcn_sched_barrier(0);
             s_next = qk(kf);
             bf16x8 pf[2];
@@ -479,7 +483,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            TETRI_T(4);
             issue_pending(1);
             // m is only a reference point, not the exact row maximum: any value keeps the result exact
             // as long as the weights stay in range.  Only when a lane's weights of this block sum to
@@ -529,9 +532,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
             // V fragments of this block: in registers before the stage may be left
             s16x8 vf[2 * DBLK];
-            TETRI_T(0);
-            TETRI_TSET(1, 0);
-            TETRI_TSET(2, 0);
             load_v(vf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
             // ---- the block after this one
             bool have_next = true, entered = false;
@@ -539,13 +539,10 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 ++kb;
             } else {
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS
-                TETRI_T(1);
-                TETRI_TSET(2, 1);
                 kb = 0;
                 nblk = 0;
                 while (nblk == 0 && it + 1 < n_stages) {
                     nblk = sync_stage(++it);
-                    TETRI_T(2);
                     if (nblk == 0) next_stage_loads(it, 0, true);
                 }
                 have_next = entered = nblk != 0;
@@ -563,13 +560,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 }
             }
             softmax_pv(s_cur, s_next, vf);
-            TETRI_T(5);
-            TETRI_ACC(0, 0, 1);     // V reads issued + (stage end) wait for them
-            TETRI_ACC(1, 1, 2);     // loads landed + barrier
-            TETRI_ACC(2, 2, 3);     // K reads issued, next loads, mask
-            TETRI_ACC(3, 3, 4);     // wait for K, QK + softmax
-            TETRI_ACC(4, 4, 5);     // check, wait for V, PV
-            TETRI_COUNT(5);
             return have_next;
         };
         f32x16 s_a = qk(kf), s_b;
@@ -580,7 +570,6 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     }
 
     TETRI_MARK(4);
-    TETRI_ACC_OUT;
     // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes.
     // The partial O goes into the stage buffer that held the stage before the last one: nobody reads
     // it any more once every wavefront has entered the last stage, so no barrier is needed before
@@ -662,11 +651,6 @@ extern "C" TETRI_API int tetri_debug_trace(unsigned long long *host, size_t coun
 {
     const size_t all = (size_t)kTraceBlocks * kTraceWaves * kTraceMarks;
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * (count < all ? count : all));
-}
-extern "C" TETRI_API int tetri_debug_phases(unsigned long long *host, size_t count)
-{
-    const size_t all = (size_t)kTraceBlocks * kTraceWaves * 8;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace2), sizeof(unsigned long long) * (count < all ? count : all));
 }
 #endif
 

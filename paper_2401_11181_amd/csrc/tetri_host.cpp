@@ -305,6 +305,16 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         // fused append: a few dozen workgroups, each copying every 64th row of the chunk
         p.append_blocks = kv_pages_w ? (p.C < 64 ? p.C : 64) : 0;
     }
+    // divisions the kernel does by launch constants, as multiplications
+    auto magic = [](uint32_t d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
+    auto log2i = [](int v) { int s = 0; while ((1 << s) < v) ++s; return s; };
+    p.hpw_shift = log2i(p.hpw);
+    p.rb_shift = log2i(p.rb);
+    p.groups = p.Hq / p.hpw;
+    p.tiles_magic = magic((uint32_t)p.tiles);
+    p.kv_magic = magic((uint32_t)(p.g / p.hpw));
+    if ((uint64_t)p.attn_grid * (uint64_t)p.tiles >= 0x100000000ull)
+        return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
     hipError_t e = split ? tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream))
                          : tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));

@@ -21,6 +21,10 @@ struct AttnParams {
     int32_t S, C, Hq, Hkv, g;
     int32_t hpw;          // query heads handled by one workgroup (they share one kv head)
     int32_t rb;           // 32-row blocks handled by one workgroup
+    int32_t hpw_shift, rb_shift;   // log2 of the two
+    int32_t groups;       // Hq / hpw: head groups, one workgroup column each
+    uint32_t tiles_magic; // ceil(2^32 / tiles), 0 for tiles == 1: division of a workgroup id by tiles
+    uint32_t kv_magic;    // the same for g / hpw: head group -> kv head
     int32_t max_blocks;
     int32_t tiles;        // upper bound of the number of row tiles of the chunk
     int32_t attn_grid;    // workgroups of the attention grid (a multiple of 8)

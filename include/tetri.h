@@ -224,9 +224,18 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
                                   int32_t num_segs, void *stream);
 
 /*
- * Kernel-variant selection for measurements.  Known keys: "attn_variant" (0 = the library chooses the
- * kernel, 1 / 2 = shared-tile kernel with 4- / 8-wavefront workgroups, 3 = key-split kernel).
- * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every variant computes the same
+ * Kernel-variant selection for measurements and tests.  Known keys:
+ *   "attn_variant"      0 = the library chooses the kernel, 1 / 2 = shared-tile kernel with 4- / 8-wavefront
+ *                       workgroups, 3 = key-split kernel;
+ *   "split_keys"        1 (default) = a launch whose row tiles would occupy at most two thirds of the
+ *                       device's compute units hands the last third of long key ranges to extra
+ *                       workgroups (the two parts of a tile meet in scratch memory the handle owns:
+ *                       launches on one handle must therefore not overlap in time), 0 = never;
+ *   "split_min_stages"  the shortest key range (in stages of 128 keys, 64 for variant 1) that is split
+ *                       (default 8, at least 2);
+ *   "split_bias_stages" stages left out when the handed-over third of a key range is measured: the extra
+ *                       work of a helper workgroup, in stages (default 5, not negative).
+ * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every setting computes the same
  * function to the same tolerance.
  */
 TETRI_API tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value);

@@ -118,6 +118,74 @@ template <int IMM> __device__ __forceinline__ void dma16_imm(const void *sbase, 
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(IMM) : "memory", "m0");
 }
+// Accesses that are coherent across the whole device by themselves (cache policy sc1: they are
+// served by the memory side, not by an XCD's L2), for data handed from one workgroup to another
+// inside a launch.  No cache write-back or invalidation is needed around them, only order:
+// coherent_stores_done() returns when this wavefront's stores have been performed.
+__device__ __forceinline__ void store_coherent(f32x4 *p, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_coherent(float *p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void coherent_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// A coherent read of one word that is not needed yet: every lane's copy of it goes to 256 bytes
+// of LDS at lds_dst; it is there after wait_vm<0>().
+__device__ __forceinline__ void peek_coherent(const void *p, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off sc1" ::"v"(p), "s"(lds_dst) : "memory", "m0");
+}
+// A partial result read back in one go: n 16-byte vectors 1 KB apart from `po` on, two floats 128
+// bytes apart at `ps`; one round trip to memory, all loads in flight together.  (One assembly
+// statement including the wait: the registers are written long after the loads are issued, which
+// the compiler must not get a chance to forget.)
+__device__ __forceinline__ void load_partial(const f32x4 *po, const float *ps, f32x4 (&x)[16], float &a, float &b)
+{
+    const f32x4 *p1 = po + 4 * 64, *p2 = po + 8 * 64, *p3 = po + 12 * 64;
+    asm volatile("global_load_dword %16, %22, off sc1\n\t"
+                 "global_load_dword %17, %22, off offset:128 sc1\n\t"
+                 "global_load_dwordx4 %0, %18, off sc1\n\t"
+                 "global_load_dwordx4 %1, %18, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %2, %18, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %3, %18, off offset:3072 sc1\n\t"
+                 "global_load_dwordx4 %4, %19, off sc1\n\t"
+                 "global_load_dwordx4 %5, %19, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %6, %19, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %7, %19, off offset:3072 sc1\n\t"
+                 "global_load_dwordx4 %8, %20, off sc1\n\t"
+                 "global_load_dwordx4 %9, %20, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %10, %20, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %11, %20, off offset:3072 sc1\n\t"
+                 "global_load_dwordx4 %12, %21, off sc1\n\t"
+                 "global_load_dwordx4 %13, %21, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %14, %21, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %15, %21, off offset:3072 sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7]),
+                   "=&v"(x[8]), "=&v"(x[9]), "=&v"(x[10]), "=&v"(x[11]), "=&v"(x[12]), "=&v"(x[13]), "=&v"(x[14]), "=&v"(x[15]),
+                   "=&v"(a), "=&v"(b)
+                 : "v"(po), "v"(p1), "v"(p2), "v"(p3), "v"(ps) : "memory");
+}
+__device__ __forceinline__ void load_partial(const f32x4 *po, const float *ps, f32x4 (&x)[8], float &a, float &b)
+{
+    const f32x4 *p1 = po + 4 * 64;
+    asm volatile("global_load_dword %8, %12, off sc1\n\t"
+                 "global_load_dword %9, %12, off offset:128 sc1\n\t"
+                 "global_load_dwordx4 %0, %10, off sc1\n\t"
+                 "global_load_dwordx4 %1, %10, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %2, %10, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %3, %10, off offset:3072 sc1\n\t"
+                 "global_load_dwordx4 %4, %11, off sc1\n\t"
+                 "global_load_dwordx4 %5, %11, off offset:1024 sc1\n\t"
+                 "global_load_dwordx4 %6, %11, off offset:2048 sc1\n\t"
+                 "global_load_dwordx4 %7, %11, off offset:3072 sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7]),
+                   "=&v"(a), "=&v"(b)
+                 : "v"(po), "v"(p1), "v"(ps) : "memory");
+}
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;

@@ -186,38 +186,56 @@ __device__ __forceinline__ void append_rows(const AttnParams &p, int blk, int nb
     }
 }
 
-template <int D, int KS>
-__global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
+// The launch parameters as the jobs of a workgroup read them: from a copy in LDS (the kernel
+// argument segment is host memory, one read of it per launch is enough), word by word into
+// scalar registers, anew by every job and once more after a job's main loop, so that they do not
+// occupy scalar registers across the loop.
+__device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
 {
+    static_assert(sizeof(AttnParams) % 4 == 0, "copied as 32-bit words");
+    constexpr int N = sizeof(AttnParams) / 4;
+    uint32_t w[N];
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(lds_copy);
+#pragma unroll
+    for (int i = 0; i < N; ++i) w[i] = __builtin_amdgcn_readfirstlane(src[i]);
+    return __builtin_bit_cast(AttnParams, w);
+}
+
+// One piece of one row tile of one head group: `piece` 0 is the whole key range, or, when the
+// launch splits key ranges (p.tail_q8 != 0), all but its last third; piece 1 is that last third.
+// The two pieces of a split tile meet through the launch's scratch memory: each wavefront stores
+// its unnormalised (O, m, row sum), and the one that finds the other's already there merges and
+// writes the output rows.  Nobody waits for anybody.
+template <int D, int KS>
+__device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_job, const AttnParams *params, uint4 *smem, float (*Mstat)[2][32],
+                                         uint32_t (*peek)[64], int grp, int tile_index, int piece)
+{
+    // a workgroup's first job starts from the kernel arguments themselves: the copy in LDS is only
+    // known to be complete after the job's first barrier
+    AttnParams p = kernarg;
+    if (!first_job) {
+        asm volatile("" ::: "memory");               // keeps this a branch: the reads are not done speculatively
+        p = read_params(params);
+    }
+
     constexpr int CH = D / 8;        // 16-byte chunks per K/V row
     constexpr int KSTEPS = D / 16;   // MFMA steps over d for S^T
     constexpr int DBLK = D / 32;     // 32-row blocks of O^T
     constexpr int NKB = kBNW / 32;   // 32-key blocks of S^T per wavefront per stage
     constexpr int STAGE = kBNW * KS; // keys per stage
     constexpr int STAGE_U4 = STAGE * CH;
-    __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stage buffers: K0 | K1 | V0 | V1
-    __shared__ float Mstat[kSlots][2][32];
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    // The thread id is made opaque per job: values derived from it are then computed where a job
+    // needs them instead of being kept in registers across the whole job loop.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = wave % kSlots, kq = wave / kSlots;    // row/head slot, key part
     const int half = lane >> 5, l32 = lane & 31;
     const int BM = 32 << p.rb_shift;
     const int S = p.S;
-    TETRI_MARK(0);
-
-    // ---- workgroups past the attention grid copy the chunk's new K/V rows into their page slots
-    // (fused KV append; they land on CUs the attention grid leaves idle or finish in its tail)
-    if ((int)blockIdx.x >= p.attn_grid) {
-        append_rows<D>(p, blockIdx.x - p.attn_grid, gridDim.x - p.attn_grid, tid, kSlots * KS * 64);
-        return;
-    }
-    // ---- workgroup id -> (head group, row tile); a head group's tiles share one XCD
-    const int per_xcd = p.attn_grid / kXcd;
-    const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
-    if (logical >= p.tiles * p.groups) return;
-    const int grp = magic_div(logical, p.tiles_magic);
-    int tile = p.tiles - 1 - (logical - grp * p.tiles);    // late (long) tiles first
+    int tile = tile_index;
 
     // ---- which (segment, row tile) is it?  Tiles never span two segments.  64 segments are
     // examined at a time: lane l takes segment s0 + l, a wave-wide prefix sum of the tile counts
@@ -258,7 +276,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     if (t0 < 0) {
         // padding rows [cu[S], C): written as +0
         const int r0 = p.cu[S] + tile * BM + 32 * rbk;
-        if (r0 >= p.C || kq != 0) return;
+        if (r0 >= p.C || kq != 0 || piece != 0) return;
         const int r = r0 + l32;
         if (r < p.C) {
             uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + head) * D);
@@ -274,7 +292,15 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     ks.n_new = min(n_s, t0 + BM);                      // new keys any row of this tile may see
     ks.n_ctx_tiles = (L + STAGE - 1) / STAGE;
     ks.max_blocks = p.max_blocks;
-    const int n_stages = ks.n_ctx_tiles + (ks.n_new + STAGE - 1) / STAGE;
+    const int n_all = ks.n_ctx_tiles + (ks.n_new + STAGE - 1) / STAGE;
+    // 0 when the launch does not split, and for key ranges too short to be worth a hand-over.  A
+    // helper has about split_bias stages' worth of extra work (a second tile's prologue, handing
+    // its first result over): the three workgroups of two tiles finish together when each tile
+    // hands over a third of what exceeds that.
+    const int n_tail = n_all >= p.split_min ? (max(n_all - p.split_bias, 0) * p.tail_q8 + 128) >> 8 : 0;
+    if (piece != 0 && n_tail == 0) return;
+    const int it_begin = piece == 0 ? 0 : n_all - n_tail;
+    const int n_stages = piece == 0 ? n_all - n_tail : n_all;          // end of this piece's stage range
 
     const int tw0 = t0 + 32 * rbk;         // first local row of this wavefront
     const int t = tw0 + l32;               // local row of this lane's query
@@ -303,9 +329,14 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // is served first), so they issue the loads of their partner in part 1 as well.
     StageLoads sl;
     if (kq == 0) {
+        if (it_begin != 0) {                         // the lookup fetched the pages of stage 0
+            page = load_stage_page<KS>(ks, it_begin, wave);
+            page_hi = load_stage_page<KS>(ks, it_begin, wave + kSlots);
+        }
 #pragma unroll
         for (int part = 0; part < KS; ++part) {
-            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, part == 0 ? page : page_hi, 0, wave + part * kSlots, new_row_bytes, smem_lds, sl);
+            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, part == 0 ? page : page_hi, it_begin, wave + part * kSlots, new_row_bytes,
+                                                          smem_lds + (it_begin & 1) * STAGE_BYTES, sl);
             issue_stage_loads<D, KS>(sl, full, lane);
         }
     }
@@ -316,7 +347,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // of a SIMD use different ones), so that at any time most wavefronts are computing.
     bool pend = false;                               // the next stage's loads are described in sl, not issued
     const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
-    page = load_stage_page<KS>(ks, 1, wave);
+    page = load_stage_page<KS>(ks, it_begin + 1, wave);
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7].  Lanes
     // past the segment's last row read its first row instead: their results are never stored.
@@ -436,9 +467,9 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // runs on the VALU, the matrix cores compute the scores of block b+1; then O += V_b P_b.
     // Every wavefront enters every stage exactly once (one barrier each), whether or not it has
     // blocks there.
-    int it = 0;
+    int it = it_begin;
     TETRI_MARK(2);
-    int nblk = sync_stage(0);
+    int nblk = sync_stage(it);
     TETRI_MARK(3);
     while (nblk == 0 && it + 1 < n_stages) {
         next_stage_loads(it, 0, false);
@@ -575,8 +606,12 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // it any more once every wavefront has entered the last stage, so no barrier is needed before
     // writing.  Its K region takes slots 0 and 1, its V region slots 2 and 3; lane l's four
     // consecutive accumulator elements are one 16-byte unit.
+    // A split tile: is the other piece there already?  The answer travels while the key parts merge.
+    asm volatile("" ::: "memory");                   // a fresh read, not the values from before the loop
+    const AttnParams pe = read_params(params);
+    const size_t unit = ((size_t)grp * pe.tiles + tile_index) * kSlots + slot;
+    if (n_tail != 0 && kq == 0 && wave_has_rows) peek_coherent(pe.counters + unit, lds_address(peek[slot]));
     float ltot = half_swap_sum(lsum);
-    float w0 = 1.f;
     if constexpr (KS == 2) {
         static_assert(2 * (DBLK * 16 * 64 * 4) == STAGE_BYTES, "two slots per matrix region");
         char *dead = reinterpret_cast<char *>(smem) + (n_stages & 1) * STAGE_BYTES + (slot >> 1) * (2 * STAGE_BYTES);
@@ -598,13 +633,10 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         if (kq == 1) return;
         const float m1 = Mstat[slot][0][l32], l1 = Mstat[slot][1][l32];
         const float mstar = fmaxf(m, m1);
-        w0 = __builtin_amdgcn_exp2f(m - mstar);
-        float w1 = __builtin_amdgcn_exp2f(m1 - mstar);
+        const float w0 = __builtin_amdgcn_exp2f(m - mstar), w1 = __builtin_amdgcn_exp2f(m1 - mstar);
         ltot = ltot * w0 + l1 * w1;
-        const float inv = __builtin_amdgcn_rcpf(ltot);
-        w0 *= inv;
-        w1 *= inv;
-        if (!row_ok) return;
+        m = mstar;
+        if (!wave_has_rows) return;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -614,26 +646,121 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 for (int e = 0; e < 4; ++e) o[db][q4 * 4 + e] = o[db][q4 * 4 + e] * w0 + x[e] * w1;
             }
     } else {
-        if (!row_ok) return;
-        w0 = __builtin_amdgcn_rcpf(ltot);
+        if (!wave_has_rows) return;
+    }
+
+    // ---- a split tile: if the other piece is there, merge with it; else leave (O, m, row sum) in
+    // the scratch memory and announce it, which tells whether the other piece has arrived in the
+    // meantime.  unit = (head group, tile, slot); the counter of a unit goes 0 -> 1 -> 0.
+    if (n_tail != 0) {
+        constexpr size_t UNIT_BYTES = (size_t)DBLK * 4 * 64 * 16 + 2 * 32 * 4;
+        const size_t units = (size_t)pe.groups * pe.tiles * kSlots;
+        char *mine = pe.scratch + ((size_t)piece * units + unit) * UNIT_BYTES;
+        const char *other = pe.scratch + ((size_t)(1 - piece) * units + unit) * UNIT_BYTES;
+        wait_vm<0>();
+        if (__builtin_amdgcn_readfirstlane(peek[slot][lane]) == 0) {
+            f32x4 *po = reinterpret_cast<f32x4 *>(mine);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
+                    store_coherent(po + (db * 4 + q4) * 64 + lane, x);
+                }
+            float *ps = reinterpret_cast<float *>(mine + (size_t)DBLK * 4 * 64 * 16);
+            if (half == 0) { store_coherent(ps + l32, m); store_coherent(ps + 32 + l32, ltot); }
+            coherent_stores_done();                  // this wavefront's partial is in memory ...
+            int arrived = 0;
+            if (lane == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
+            arrived = __builtin_amdgcn_readfirstlane(arrived);
+            if (arrived == 0) return;                // first of the two: the other piece finishes the tile
+        }
+        if (lane == 0) pe.counters[unit] = 0;        // ready for the next launch
+        const f32x4 *qo = reinterpret_cast<const f32x4 *>(other);
+        const float *qs = reinterpret_cast<const float *>(other + (size_t)DBLK * 4 * 64 * 16);
+        // The result must not depend on which piece arrives last: both evaluate
+        // fma(piece 1, its weight, piece 0 * its weight).
+        float m1, l1;
+        f32x4 x[DBLK * 4];
+        load_partial(qo + lane, qs + l32, x, m1, l1);
+        const float mstar = fmaxf(m, m1);
+        const float w_own = __builtin_amdgcn_exp2f(m - mstar), w_oth = __builtin_amdgcn_exp2f(m1 - mstar);
+        ltot = piece == 0 ? __builtin_fmaf(l1, w_oth, ltot * w_own) : __builtin_fmaf(ltot, w_own, l1 * w_oth);
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= w0;
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
+                    o[db][q4 * 4 + e] = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
+                }
     }
 
-    // ---- store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
-    uint16_t *orow = p.out + ((size_t)(ks.row_base + t) * p.Hq + head) * D;
+    // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
+    if (!row_ok) return;
+    const float inv = __builtin_amdgcn_rcpf(ltot);
+    uint16_t *orow = pe.out + ((size_t)(ks.row_base + t) * pe.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             bf16x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)o[db][q4 * 4 + e];
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
             *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
         }
     TETRI_MARK(6);
+}
+
+template <int D, int KS>
+__global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
+{
+    constexpr int STAGE_U4 = kBNW * KS * (D / 8);
+    __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stage buffers: K0 | K1 | V0 | V1
+    __shared__ float Mstat[kSlots][2][32];
+    __shared__ uint32_t peek[kSlots][64];            // where a look at a split tile's arrival counter lands
+    __shared__ AttnParams params;
+    TETRI_MARK(0);
+
+    // ---- workgroups past the attention grid copy the chunk's new K/V rows into their page slots
+    // (fused KV append; they land on CUs the attention grid leaves idle or finish in its tail)
+    if ((int)blockIdx.x >= p.attn_grid) {
+        append_rows<D>(p, blockIdx.x - p.attn_grid, gridDim.x - p.attn_grid, threadIdx.x, kSlots * KS * 64);
+        return;
+    }
+    // ---- workgroup id -> (head group, job).  The workgroups of a head group run on one XCD (they
+    // read the same K and V through its L2); an XCD has gpx groups and starts their workgroups job
+    // by job.  Without key-range splitting the jobs of a group are its row tiles, late (long) ones
+    // first.  With it (helpers != 0): first the tiles but the last one of the host's bound (which
+    // exists only if the chunk has ragged segments), then the helpers, each doing the last third
+    // of the key ranges of two of those tiles, then that last tile and its helper: what is
+    // probably empty starts last.
+    const int xcd = blockIdx.x % kXcd, local = blockIdx.x / kXcd;
+    const int job = magic_div(local, p.gpx_magic);
+    const int grp = xcd * p.gpx + (local - job * p.gpx);
+    const int T = p.tiles, H = p.helpers;
+    if (grp >= p.groups || job >= T + H) return;
+    if (threadIdx.x == 0) params = p;                // from scalar registers: no memory read to wait for
+    int piece = 0, first = T - 1 - job, count = 1;
+    if (H != 0) {
+        if (job < T - 1) {
+            first = T - 2 - job;
+        } else if (job < T + H - 2) {
+            piece = 1;
+            first = T - 2 - 2 * (job - (T - 1));
+            count = min(2, first + 1);
+        } else {
+            piece = job - (T + H - 2);
+            first = T - 1;
+        }
+    }
+    for (int i = 0; i < count; ++i) {
+        if (i != 0) __syncthreads();                 // the stage buffers change hands
+        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, first - i, piece);
+    }
 }
 
 template <int D, int KS>

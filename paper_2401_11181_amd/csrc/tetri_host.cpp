@@ -77,15 +77,53 @@ tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
     tetri_ctx *h = new (std::nothrow) tetri_ctx;
     if (!h) return fail(nullptr, TETRI_ERR_NOMEM, "tetri_create: out of host memory");
     h->cfg = *c;
+    // Scratch memory for launches that split key ranges: such a launch has at most one workgroup
+    // per CU, 4 (row block, head) slots each, two pieces per slot; a piece is O (32 x head_dim
+    // floats), m and the row sum.
+    hipDeviceProp_t prop;
+    if ((e = hipGetDevice(&h->device)) != hipSuccess || (e = hipGetDeviceProperties(&prop, h->device)) != hipSuccess) {
+        delete h;
+        return fail(nullptr, TETRI_ERR_HIP, "tetri_create: %s", hipGetErrorString(e));
+    }
+    h->num_cus = prop.multiProcessorCount;
+    h->scratch_units = (size_t)h->num_cus * 4;
+    h->unit_bytes = (size_t)32 * c->head_dim * 4 + 2 * 32 * 4;
+    if ((e = hipMalloc(reinterpret_cast<void **>(&h->scratch), 2 * h->scratch_units * h->unit_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void **>(&h->counters), h->scratch_units * sizeof(int32_t))) != hipSuccess ||
+        (e = hipMemset(h->counters, 0, h->scratch_units * sizeof(int32_t))) != hipSuccess) {
+        tetri_destroy(h);
+        return fail(nullptr, TETRI_ERR_HIP, "tetri_create: scratch memory: %s", hipGetErrorString(e));
+    }
     *out = h;
     return TETRI_OK;
 }
 
-void tetri_destroy(tetri_ctx *ctx) { delete ctx; }
+void tetri_destroy(tetri_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    delete ctx;
+}
 
 tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
 {
     if (!ctx || !key) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: null argument");
+    if (std::strcmp(key, "split_keys") == 0) {
+        if (value < 0 || value > 1) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_keys=%d (0 or 1)", value);
+        ctx->split_keys = value;
+        return TETRI_OK;
+    }
+    if (std::strcmp(key, "split_min_stages") == 0) {
+        if (value < 2) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_min_stages=%d (at least 2)", value);
+        ctx->split_min_stages = value;
+        return TETRI_OK;
+    }
+    if (std::strcmp(key, "split_bias_stages") == 0) {
+        if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_bias_stages=%d (not negative)", value);
+        ctx->split_bias_stages = value;
+        return TETRI_OK;
+    }
     if (std::strcmp(key, "attn_variant") == 0) {
         if (value < 0 || value > 3) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
         ctx->attn_variant = value;
@@ -298,10 +336,23 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         p.tiles = tile_bound(p.C, p.S, 32);
         p.attn_grid = (p.tiles * p.Hq + 7) / 8 * 8;
         p.append_blocks = 0;
+        p.helpers = 0;
+        p.gpx = 1;
     } else {
         wave_grouping(p.g, &p.hpw, &p.rb);
         p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
-        p.attn_grid = (p.tiles * (p.Hq / p.hpw) + 7) / 8 * 8;
+        // A launch whose tiles would occupy at most two thirds of the CUs gets one more workgroup
+        // per two tiles: it takes the last third of their key ranges, which shortens the longest
+        // workgroup by a third.
+        // The last tile of the bound and its helper exist only in chunks with ragged segments and
+        // are not counted.
+        const int groups = p.Hq / p.hpw;
+        p.helpers = p.tiles / 2 + 1;
+        if (!h->split_keys || (p.tiles - 1 + p.helpers - 1) * groups > h->num_cus || p.tiles < 2 ||
+            (size_t)p.tiles * groups * 4 > h->scratch_units)
+            p.helpers = 0;
+        p.gpx = (groups + 7) / 8;
+        p.attn_grid = 8 * p.gpx * (p.tiles + p.helpers);
         // fused append: a few dozen workgroups, each copying every 64th row of the chunk
         p.append_blocks = kv_pages_w ? (p.C < 64 ? p.C : 64) : 0;
     }
@@ -311,9 +362,14 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     p.hpw_shift = log2i(p.hpw);
     p.rb_shift = log2i(p.rb);
     p.groups = p.Hq / p.hpw;
-    p.tiles_magic = magic((uint32_t)p.tiles);
+    p.gpx_magic = magic((uint32_t)p.gpx);
+    p.tail_q8 = p.helpers ? 85 : 0;
+    p.split_min = h->split_min_stages;
+    p.split_bias = h->split_bias_stages;
+    p.scratch = h->scratch;
+    p.counters = h->counters;
     p.kv_magic = magic((uint32_t)(p.g / p.hpw));
-    if ((uint64_t)p.attn_grid * (uint64_t)p.tiles >= 0x100000000ull)
+    if ((uint64_t)p.attn_grid * (uint64_t)(p.tiles + p.helpers) >= 0x100000000ull)
         return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
     hipError_t e = split ? tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream))
                          : tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));

@@ -10,6 +10,14 @@ struct tetri_ctx {
     tetri_config cfg;
     std::string err;
     int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts, 3 = key-split kernel
+    int split_keys = 1;     // 1 = launches that would leave a third of the CUs idle split the key ranges of their tiles
+    int split_min_stages = 8;   // ... those of at least this many stages
+    int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
+    int device = 0;         // the device the handle was created on; its scratch memory lives there
+    int num_cus = 0;
+    char *scratch = nullptr;        // partial results of split tiles: 2 pieces x scratch_units units
+    int32_t *counters = nullptr;    // scratch_units arrival counters, zero between launches
+    size_t scratch_units = 0, unit_bytes = 0;
 };
 
 // Launch parameters of the attention kernels (passed by value).
@@ -23,7 +31,14 @@ struct AttnParams {
     int32_t rb;           // 32-row blocks handled by one workgroup
     int32_t hpw_shift, rb_shift;   // log2 of the two
     int32_t groups;       // Hq / hpw: head groups, one workgroup column each
-    uint32_t tiles_magic; // ceil(2^32 / tiles), 0 for tiles == 1: division of a workgroup id by tiles
+    int32_t helpers;      // per head group: workgroups that take the last third of two tiles' key ranges (0: no split)
+    int32_t tail_q8;      // the share of a tile's stages that goes to its helper, in 1/256 (0: no split)
+    int32_t split_min;    // only key ranges of at least this many stages are split
+    int32_t split_bias;   // stages not counted when a key range's last third is measured
+    int32_t gpx;          // head groups per XCD
+    uint32_t gpx_magic;   // ceil(2^32 / gpx), 0 for 1
+    char *scratch;        // partial results of split tiles
+    int32_t *counters;    // one per (group, tile, slot), all zero between launches
     uint32_t kv_magic;    // the same for g / hpw: head group -> kv head
     int32_t max_blocks;
     int32_t tiles;        // upper bound of the number of row tiles of the chunk

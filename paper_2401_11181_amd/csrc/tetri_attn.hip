@@ -160,29 +160,44 @@ __device__ __forceinline__ int load_stage_page(const KeySource &ks, int it, int 
 // Fused KV append: workgroup `blk` of `nblk` copies chunk rows blk, blk + nblk, ... (K and V of
 // every kv head, 16 bytes per thread and pass) into slot (ctx + t) % 16 of page
 // block_table[s][(ctx + t) / 16].  Same result as the stand-alone append kernel, bit for bit.
+// First every thread looks up where one of the workgroup's rows goes (table in LDS); then rows
+// are copied 8 at a time with all their loads issued before the first store, so that a
+// workgroup has tens of KB in flight.
 template <int D>
-__device__ __forceinline__ void append_rows(const AttnParams &p, int blk, int nblk, int tid, int nthreads)
+__device__ __forceinline__ void append_rows(const AttnParams &p, unsigned long long *row_dst, int blk, int nblk, int tid, int nthreads)
 {
-    constexpr int CH = D / 8;
+    constexpr int CH = D / 8, R = 8;
     const int n_real = p.cu[p.S];
     const int per_row = p.Hkv * CH;                    // 16-byte vectors per row and matrix
-    for (int row = blk; row < n_real; row += nblk) {
-        int lo = 0, hi = p.S - 1;                      // largest s with cu[s] <= row (uniform)
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (p.cu[mid] <= row) lo = mid; else hi = mid - 1;
+    for (int base = blk; base < n_real; base += nblk * nthreads) {     // one pass unless the chunk has more than nblk * nthreads rows
+        const int mine = base + tid * nblk;
+        if (mine < n_real) {
+            int lo = 0, hi = p.S - 1;                  // largest s with cu[s] <= row
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (p.cu[mid] <= mine) lo = mid; else hi = mid - 1;
+            }
+            const int pos = p.ctx[lo] + (mine - p.cu[lo]);
+            const int page = p.bt[(size_t)lo * p.max_blocks + pos / kPage];
+            // of the row's K vector 0 of head 0, in 16-byte units
+            row_dst[tid] = (unsigned long long)page * 2 * p.Hkv * (kPage * CH) + (unsigned long long)(pos % kPage) * CH;
         }
-        const int pos = p.ctx[lo] + (row - p.cu[lo]);
-        const int page = p.bt[(size_t)lo * p.max_blocks + pos / kPage];
-        const int slot = pos % kPage;
-        for (int x = tid; x < 2 * per_row; x += nthreads) {
-            const int which = x >= per_row, y = x - which * per_row;
-            const int head = y / CH, c = y - head * CH;
-            const uint4 *src = reinterpret_cast<const uint4 *>(which ? p.v_new : p.k_new) + (size_t)row * per_row + y;
-            uint4 *dst = reinterpret_cast<uint4 *>(p.pages_w) +
-                         (((size_t)page * 2 + which) * p.Hkv + head) * (kPage * CH) + (size_t)slot * CH + c;
-            *dst = *src;
+        __syncthreads();
+        const int rows_here = min(nthreads, (n_real - base + nblk - 1) / nblk);
+        for (int r0 = 0; r0 < rows_here; r0 += R) {
+            for (int x = tid; x < 2 * per_row; x += nthreads) {
+                const int which = x >= per_row, y = x - which * per_row;
+                const int head = y / CH, c = y - head * CH;
+                const size_t in_page = ((size_t)which * p.Hkv + head) * (kPage * CH) + c;
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(which ? p.v_new : p.k_new) + y;
+                u32x4 v[R];                            // past the last row: that row once more
+#pragma unroll
+                for (int r = 0; r < R; ++r) v[r] = src[(size_t)(base + min(r0 + r, rows_here - 1) * nblk) * per_row];
+#pragma unroll
+                for (int r = 0; r < R; ++r) reinterpret_cast<u32x4 *>(p.pages_w)[row_dst[min(r0 + r, rows_here - 1)] + in_page] = v[r];
+            }
         }
+        __syncthreads();
     }
 }
 
@@ -725,11 +740,17 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     __shared__ AttnParams params;
     TETRI_MARK(0);
 
-    // ---- workgroups past the attention grid copy the chunk's new K/V rows into their page slots
-    // (fused KV append; they land on CUs the attention grid leaves idle or finish in its tail)
-    if ((int)blockIdx.x >= p.attn_grid) {
-        append_rows<D>(p, blockIdx.x - p.attn_grid, gridDim.x - p.attn_grid, threadIdx.x, kSlots * KS * 64);
-        return;
+    // ---- fused KV append: append_blocks workgroups copy the chunk's new K/V rows into their page
+    // slots.  They come after the attention workgroups that certainly have work (attn_first of
+    // them) and before those that probably have none, so that they start on the CUs the attention
+    // grid leaves idle instead of waiting for one to finish.
+    int abid = blockIdx.x;                           // index in the attention grid
+    if (abid >= p.attn_first) {
+        if (abid < p.attn_first + p.append_blocks) {
+            append_rows<D>(p, reinterpret_cast<unsigned long long *>(smem), abid - p.attn_first, p.append_blocks, threadIdx.x, kSlots * KS * 64);
+            return;
+        }
+        abid -= p.append_blocks;
     }
     // ---- workgroup id -> (head group, job).  The workgroups of a head group run on one XCD (they
     // read the same K and V through its L2); an XCD has gpx groups and starts their workgroups job
@@ -738,7 +759,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // exists only if the chunk has ragged segments), then the helpers, each doing the last third
     // of the key ranges of two of those tiles, then that last tile and its helper: what is
     // probably empty starts last.
-    const int xcd = blockIdx.x % kXcd, local = blockIdx.x / kXcd;
+    const int xcd = abid % kXcd, local = abid / kXcd;
     const int job = magic_div(local, p.gpx_magic);
     const int grp = xcd * p.gpx + (local - job * p.gpx);
     const int T = p.tiles, H = p.helpers;

@@ -338,6 +338,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         p.append_blocks = 0;
         p.helpers = 0;
         p.gpx = 1;
+        p.attn_first = p.attn_grid;
     } else {
         wave_grouping(p.g, &p.hpw, &p.rb);
         p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
@@ -353,8 +354,16 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
             p.helpers = 0;
         p.gpx = (groups + 7) / 8;
         p.attn_grid = 8 * p.gpx * (p.tiles + p.helpers);
+        p.attn_first = p.helpers ? 8 * p.gpx * (p.tiles + p.helpers - 2) : p.attn_grid;
         // fused append: a few dozen workgroups, each copying every 64th row of the chunk
-        p.append_blocks = kv_pages_w ? (p.C < 64 ? p.C : 64) : 0;
+        // (every workgroup of this kernel occupies a whole CU: in a launch that splits key ranges only
+        // the CUs its attention workgroups leave free take append workgroups right away)
+        int append_wgs = 64;
+        if (p.helpers) {
+            const int idle = h->num_cus - p.attn_first;
+            append_wgs = idle >= 8 ? (idle < 64 ? idle / 8 * 8 : 64) : 8;
+        }
+        p.append_blocks = kv_pages_w ? (p.C < append_wgs ? p.C : append_wgs) : 0;
     }
     // divisions the kernel does by launch constants, as multiplications
     auto magic = [](uint32_t d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };

@@ -44,6 +44,7 @@ struct AttnParams {
     int32_t tiles;        // upper bound of the number of row tiles of the chunk
     int32_t attn_grid;    // workgroups of the attention grid (a multiple of 8)
     int32_t append_blocks; // extra workgroups that do the fused KV append (0: none)
+    int32_t attn_first;   // attention workgroups that precede them in the grid (a multiple of 8)
     float c;              // |scale| * log2(e)
     int32_t neg;          // 1 if scale < 0
 };

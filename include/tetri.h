@@ -233,8 +233,9 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  *                       launches on one handle must therefore not overlap in time), 0 = never;
  *   "split_min_stages"  the shortest key range (in stages of 128 keys, 64 for variant 1) that is split
  *                       (default 8, at least 2);
- *   "split_bias_stages" stages left out when the handed-over third of a key range is measured: the extra
- *                       work of a helper workgroup, in stages (default 5, not negative).
+ *   "split_bias_stages" stages left out when the handed-over share of a key range is measured: the extra
+ *                       work of a helper workgroup, in stages (default 5, not negative);
+ *   "split_share_q8"    the share of the remaining stages that is handed over, in 1/256 (default 85: a third).
  * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every setting computes the same
  * function to the same tolerance.
  */

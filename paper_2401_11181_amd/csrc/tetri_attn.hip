@@ -216,6 +216,49 @@ __device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
     return __builtin_bit_cast(AttnParams, w);
 }
 
+// What a helper workgroup's wavefront remembers of its first tile when it goes on to its second
+// one before the hand-over of the first is settled (see tile_job).
+struct Handover {
+    int unit = -1;          // (head group, tile, slot) whose partial result is stored but not announced yet
+    int old = 0;            // lane 0: what the arrival counter held when it was announced
+    bool announced = false;
+    int seg_cu = 0, t0 = 0, n_s = 0;    // where the tile's rows are
+};
+
+// The two pieces of a split tile, merged, normalised and written.  (o, m, l): this wavefront's
+// piece; `other`: the other piece in the scratch memory.  Whichever piece calls this, the value is
+// fma(piece 1, its weight, piece 0 * its weight).
+template <int D>
+__device__ __forceinline__ void merge_pieces_and_store(f32x16 (&o)[D / 32], float m, float l, const char *other, int piece, int lane,
+                                                       bool row_ok, uint16_t *orow)
+{
+    constexpr int DBLK = D / 32;
+    const int half = lane >> 5, l32 = lane & 31;
+    const f32x4 *qo = reinterpret_cast<const f32x4 *>(other);
+    const float *qs = reinterpret_cast<const float *>(other + (size_t)DBLK * 4 * 64 * 16);
+    float m1, l1;
+    f32x4 x[DBLK * 4];
+    load_partial(qo + lane, qs + l32, x, m1, l1);
+    const float mstar = fmaxf(m, m1);
+    const float w_own = __builtin_amdgcn_exp2f(m - mstar), w_oth = __builtin_amdgcn_exp2f(m1 - mstar);
+    l = piece == 0 ? __builtin_fmaf(l1, w_oth, l * w_own) : __builtin_fmaf(l, w_own, l1 * w_oth);
+    if (!row_ok) return;
+    const float inv = __builtin_amdgcn_rcpf(l);
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
+                const float r = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
+                w[e] = (__bf16)(r * inv);
+            }
+            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
+        }
+}
+
 // One piece of one row tile of one head group: `piece` 0 is the whole key range, or, when the
 // launch splits key ranges (p.tail_q8 != 0), all but its last third; piece 1 is that last third.
 // The two pieces of a split tile meet through the launch's scratch memory: each wavefront stores
@@ -223,7 +266,7 @@ __device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
 // writes the output rows.  Nobody waits for anybody.
 template <int D, int KS>
 __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_job, const AttnParams *params, uint4 *smem, float (*Mstat)[2][32],
-                                         uint32_t (*peek)[64], int grp, int tile_index, int piece)
+                                         uint32_t (*peek)[64], int grp, int tile_index, int piece, Handover &ho, bool may_defer)
 {
     // a workgroup's first job starts from the kernel arguments themselves: the copy in LDS is only
     // known to be complete after the job's first barrier
@@ -485,6 +528,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     int it = it_begin;
     TETRI_MARK(2);
     int nblk = sync_stage(it);
+    if (ho.unit >= 0 && !ho.announced) {
+        // the previous tile's partial result was stored before this job began; the wait in front of
+        // the barrier just passed covered those stores, so it can be announced now.  What the
+        // counter held is looked at when this job is done.
+        if (lane == 0) ho.old = atomicAdd(p.counters + ho.unit, 1);
+        ho.announced = true;
+    }
     TETRI_MARK(3);
     while (nblk == 0 && it + 1 < n_stages) {
         next_stage_loads(it, 0, false);
@@ -686,6 +736,14 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 }
             float *ps = reinterpret_cast<float *>(mine + (size_t)DBLK * 4 * 64 * 16);
             if (half == 0) { store_coherent(ps + l32, m); store_coherent(ps + 32 + l32, ltot); }
+            if (may_defer) {
+                // a helper with a second tile to do: neither the end of the stores nor the answer of
+                // the arrival counter is waited for here (about 4 us)
+                ho.unit = (int)unit;
+                ho.announced = false;
+                ho.seg_cu = seg_cu; ho.t0 = t0; ho.n_s = n_s;
+                return;
+            }
             coherent_stores_done();                  // this wavefront's partial is in memory ...
             int arrived = 0;
             if (lane == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
@@ -693,25 +751,8 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             if (arrived == 0) return;                // first of the two: the other piece finishes the tile
         }
         if (lane == 0) pe.counters[unit] = 0;        // ready for the next launch
-        const f32x4 *qo = reinterpret_cast<const f32x4 *>(other);
-        const float *qs = reinterpret_cast<const float *>(other + (size_t)DBLK * 4 * 64 * 16);
-        // The result must not depend on which piece arrives last: both evaluate
-        // fma(piece 1, its weight, piece 0 * its weight).
-        float m1, l1;
-        f32x4 x[DBLK * 4];
-        load_partial(qo + lane, qs + l32, x, m1, l1);
-        const float mstar = fmaxf(m, m1);
-        const float w_own = __builtin_amdgcn_exp2f(m - mstar), w_oth = __builtin_amdgcn_exp2f(m1 - mstar);
-        ltot = piece == 0 ? __builtin_fmaf(l1, w_oth, ltot * w_own) : __builtin_fmaf(ltot, w_own, l1 * w_oth);
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
-                    o[db][q4 * 4 + e] = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
-                }
+        merge_pieces_and_store<D>(o, m, ltot, other, piece, lane, row_ok, pe.out + ((size_t)(ks.row_base + t) * pe.Hq + head) * D);
+        return;
     }
 
     // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
@@ -778,9 +819,42 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             first = T - 1;
         }
     }
+    Handover ho;
     for (int i = 0; i < count; ++i) {
         if (i != 0) __syncthreads();                 // the stage buffers change hands
-        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, first - i, piece);
+        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, first - i, piece, ho, i + 1 < count);
+    }
+    // ---- a helper's first tile whose hand-over was left open: if the other piece has arrived in the
+    // meantime (it found the counter at 0 and went away), this wavefront finishes the tile from its
+    // own stored partial result.
+    if (ho.unit >= 0) {
+        constexpr int DBLK = D / 32;
+        constexpr size_t UNIT_BYTES = (size_t)DBLK * 4 * 64 * 16 + 2 * 32 * 4;
+        asm volatile("" ::: "memory");
+        const AttnParams pd = read_params(&params);
+        const int lane = threadIdx.x & 63;
+        if (!ho.announced) {                         // the second job ended before its first barrier
+            wait_vm<0>();
+            if (lane == 0) ho.old = atomicAdd(pd.counters + ho.unit, 1);
+        }
+        if (__builtin_amdgcn_readfirstlane(ho.old) != 0) {
+            if (lane == 0) pd.counters[ho.unit] = 0;
+            const size_t units = (size_t)pd.groups * pd.tiles * kSlots;
+            const char *mine = pd.scratch + (units + ho.unit) * UNIT_BYTES;          // piece 1
+            const char *other = pd.scratch + (size_t)ho.unit * UNIT_BYTES;           // piece 0
+            f32x4 x[DBLK * 4];
+            float m, l;
+            load_partial(reinterpret_cast<const f32x4 *>(mine) + lane, reinterpret_cast<const float *>(mine + (size_t)DBLK * 4 * 64 * 16) + (lane & 31), x, m, l);
+            f32x16 o[DBLK];
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] = x[db * 4 + v / 4][v % 4];
+            const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), slot = wave % kSlots;
+            const int head = grp * pd.hpw + (slot & (pd.hpw - 1));
+            const int t = ho.t0 + 32 * (slot >> pd.hpw_shift) + (lane & 31);
+            merge_pieces_and_store<D>(o, m, l, other, 1, lane, t < ho.n_s, pd.out + ((size_t)(ho.seg_cu + t) * pd.Hq + head) * D);
+        }
     }
 }
 

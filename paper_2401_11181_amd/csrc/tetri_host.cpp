@@ -124,6 +124,11 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         ctx->split_bias_stages = value;
         return TETRI_OK;
     }
+    if (std::strcmp(key, "split_share_q8") == 0) {
+        if (value < 1 || value > 128) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_share_q8=%d (1..128)", value);
+        ctx->split_share_q8 = value;
+        return TETRI_OK;
+    }
     if (std::strcmp(key, "attn_variant") == 0) {
         if (value < 0 || value > 3) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
         ctx->attn_variant = value;
@@ -372,7 +377,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     p.rb_shift = log2i(p.rb);
     p.groups = p.Hq / p.hpw;
     p.gpx_magic = magic((uint32_t)p.gpx);
-    p.tail_q8 = p.helpers ? 85 : 0;
+    p.tail_q8 = p.helpers ? h->split_share_q8 : 0;
     p.split_min = h->split_min_stages;
     p.split_bias = h->split_bias_stages;
     p.scratch = h->scratch;

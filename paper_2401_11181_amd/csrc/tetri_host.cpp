@@ -357,6 +357,12 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         if (!h->split_keys || (p.tiles - 1 + p.helpers - 1) * groups > h->num_cus || p.tiles < 2 ||
             (size_t)p.tiles * groups * 4 > h->scratch_units)
             p.helpers = 0;
+        if (p.helpers) {
+            // the scratch memory lives on the device the handle was created on
+            int dev = -1;
+            if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+                return fail(h, TETRI_ERR_INVALID_ARG, "%s: the current device is %d, the handle was created on device %d", fn, dev, h->device);
+        }
         p.gpx = (groups + 7) / 8;
         p.attn_grid = 8 * p.gpx * (p.tiles + p.helpers);
         p.attn_first = p.helpers ? 8 * p.gpx * (p.tiles + p.helpers - 2) : p.attn_grid;

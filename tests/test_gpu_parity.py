@@ -15,11 +15,11 @@ pytestmark = pytest.mark.gpu
 
 # attention kernel variants: 0 = library's choice, 1 / 2 = shared-tile kernel with 4 / 2 wavefronts,
 # 3 = key-split kernel; 10 / 11 = kernels 0 / 1 handing the last third of every key range of two or
-# more stages to a second workgroup, 12 = kernel 0 never doing so.  Every variant must meet the same bar.
-VARIANTS = [0, 1, 2, 3, 10, 11, 12]
+# more stages to a second workgroup (13: half of it), 12 = kernel 0 never doing so.  Every variant must meet the same bar.
+VARIANTS = [0, 1, 2, 3, 10, 11, 12, 13]
 
 
-@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "split", "handover", "handover4", "whole"])
+@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "split", "handover", "handover4", "whole", "handover-half"])
 def variant(request):
     return request.param
 

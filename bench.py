@@ -10,6 +10,7 @@ a time).  Q/K/V of every chunk and the page pool are resident in HBM before the 
 Prints ONE JSON line.  `value` = algorithmic attention flops of a step / step time.
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -38,6 +39,11 @@ def main():
                     help="finish with one 256 MiB device-to-device copy (known traffic, to calibrate HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
+    ap.add_argument("--policy", default=None, choices=["fcfs", "sjf", "ljf"],
+                    help="order the workload's requests with tetri_schedule (Sec. 3.3.2) before packing")
+    ap.add_argument("--sched-batch", type=int, default=0, help="PrefillSchedBatch: requests per sorted group (0: all)")
+    ap.add_argument("--chunk-size", type=int, default=None, help="ChunkSize override (the saturation sweep of Sec. 2.2)")
+    ap.add_argument("--prompt-len", type=int, default=None, help="replace the workload's prompts by one prompt of this length")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -56,6 +62,15 @@ def main():
     torch.cuda.set_device(0)
 
     w = synth.workload(args.workload)
+    if args.prompt_len is not None:
+        w = dataclasses.replace(w, name=w.name + "-len%d" % args.prompt_len, prompt_lens=[args.prompt_len], order=[0],
+                                num_pages=max(w.num_pages, -(-args.prompt_len // w.page_size) + 64))
+    if args.chunk_size is not None:
+        w = dataclasses.replace(w, name=w.name + "-chunk%d" % args.chunk_size, chunk_size=args.chunk_size)
+    if args.policy is not None:
+        order = tetri.tetri_schedule(w.prompt_lens, {"fcfs": tetri.TETRI_FCFS, "sjf": tetri.TETRI_SJF, "ljf": tetri.TETRI_LJF}[args.policy],
+                                     args.sched_batch)
+        w = dataclasses.replace(w, name="%s-%s%d" % (w.name, args.policy, args.sched_batch), order=[int(x) for x in order])
     tables = synth.place_pages(w)
     pipe = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                            w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
@@ -168,6 +183,8 @@ def main():
                                                            w.num_q_heads, w.head_dim, w.num_kv_heads, w.page_size,
                                                            w.seed),
             "chunk_size": C, "launch_mode": args.mode,
+            "segments_per_chunk": {"mean": round(float(np.mean([len(pipe.chunk_segments(c)) for c in range(nC)])), 2),
+                                   "max": int(max(len(pipe.chunk_segments(c)) for c in range(nC)))},
             "step": "pack + metadata + upload + per chunk " +
                     ("(attention launch, kv append launch)" if args.two_launches else "one fused attention+append launch"),
         },

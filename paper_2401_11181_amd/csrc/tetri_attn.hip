@@ -27,6 +27,12 @@
 //     global address of the direct load) so that the 128-bit K reads and the transposing V reads
 //     are bank-conflict free.
 //   * Workgroup ids are remapped so that all row tiles of a kv head run on one XCD (one L2).
+//   * A launch with fewer row tiles than two thirds of the CUs adds helper workgroups: a tile
+//     with a long key range hands its last stages to a helper (two tiles per helper) and the two
+//     partial results meet in scratch memory of the library's handle, without anybody waiting
+//     (tile_job, merge_pieces_and_store).
+//   * The fused form of the launch has further workgroups that copy the chunk's new K/V rows
+//     into the page pool (append_rows).
 #include "attn_common.h"
 
 namespace {

@@ -611,9 +611,6 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             }
             lsum += l_blk;
             // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7.
-#ifdef EXP_PRIO
-            __builtin_amdgcn_s_setprio(EXP_PRIO);
-#endif
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -621,9 +618,6 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
                 if (j == 0) issue_pending(2);
             }
-#ifdef EXP_PRIO
-            __builtin_amdgcn_s_setprio(0);
-#endif
         };
         // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
         // after the last block.

@@ -83,7 +83,9 @@ typedef struct {
 } tetri_segment;
 
 /*
- * Create / destroy a handle carrying the static shape.  The handle owns no device memory.
+ * Create / destroy a handle carrying the static shape.  The handle owns a fixed amount of device
+ * scratch memory (about 33 MB on a 256-CU device, allocated here, freed by tetri_destroy) on the
+ * device that is current at creation; launching calls must be made with that device current.
  * tetri_create checks the configuration (TETRI_ERR_UNSUPPORTED / TETRI_ERR_INVALID_ARG) and
  * that a HIP device is usable (TETRI_ERR_HIP) and stores the handle in *out.
  * A handle must not be used by two threads at once.
@@ -211,6 +213,39 @@ TETRI_API tetri_status tetri_chunk_prefill_attn_append(tetri_ctx *ctx, const voi
                                                        const int32_t *block_table, const int32_t *cu_chunk_q_lens,
                                                        const int32_t *ctx_lens, int32_t num_segs, float scale,
                                                        void *out, void *stream);
+
+/*
+ * KV export and import: the data plane of the dispatcher (Sec. 3.3.4 "Dispatcher": a prefilled
+ * request's KV cache is sent from the prefill instance's accelerator memory to the chosen decode
+ * instance, either request-level, i.e. the whole request after its last chunk, or chunk-level, i.e.
+ * each chunk's slice as soon as it is produced; both instances keep the cache in pages, Sec. 3.4).
+ * Both granularities are the same call with other token ranges.
+ *
+ * For request r = 0..num_reqs-1 the calls move tokens [first_r, first_r + n_r) with
+ * n_r = cu_tokens[r+1] - cu_tokens[r] and first_r = first_tokens[r] (0 if first_tokens is NULL),
+ * found in slot (pos % page_size) of page block_table[r][pos / page_size].  The transfer buffer is
+ * independent of page size and page placement: request after request a dense bf16 block
+ *     [2 (0 = K, 1 = V)][num_kv_heads][n_r][head_dim]
+ * starting at element 2 * num_kv_heads * head_dim * cu_tokens[r]; so each request's block is one
+ * contiguous message and the whole buffer has 2 * num_kv_heads * head_dim * total_tokens elements.
+ * tetri_kv_export reads the pool and writes every element of the buffer; tetri_kv_import reads the
+ * buffer and writes exactly the page slots of the token ranges (bit for bit, nothing else).
+ * With a chunk's cu_chunk_q_lens / ctx_lens / block_table as cu_tokens / first_tokens / block_table
+ * the calls move exactly what tetri_kv_append cached for that chunk.
+ *   kv_pages, buf: device (export: in, out; import: out, in).  block_table [num_reqs][max_blocks_per_seq],
+ *   cu_tokens [num_reqs + 1] (cu_tokens[0] = 0, non-decreasing), first_tokens [num_reqs] or NULL: device, in.
+ *   num_reqs: host scalar >= 1.  total_tokens: host scalar, must equal cu_tokens[num_reqs]
+ *   (it sizes the launch; 0 is allowed and launches nothing).
+ * Token ranges of one import must not overlap in the pool.  The device arrays are trusted like those of
+ * the other launching calls.  TETRI_ERR_INVALID_ARG for null / misaligned pointers and counts out of
+ * range (total_tokens above num_reqs * max_blocks_per_seq * page_size).
+ */
+TETRI_API tetri_status tetri_kv_export(tetri_ctx *ctx, const void *kv_pages, const int32_t *block_table,
+                                       const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
+                                       int64_t total_tokens, void *buf, void *stream);
+TETRI_API tetri_status tetri_kv_import(tetri_ctx *ctx, const void *buf, const int32_t *block_table,
+                                       const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
+                                       int64_t total_tokens, void *kv_pages, void *stream);
 
 /*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to

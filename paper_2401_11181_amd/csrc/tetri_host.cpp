@@ -309,6 +309,54 @@ tetri_status tetri_kv_append(tetri_ctx *h, const void *k_new, const void *v_new,
     return TETRI_OK;
 }
 
+static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, void *buf, const int32_t *block_table,
+                                const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
+                                int64_t total_tokens, bool to_pool, void *stream)
+{
+    if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
+    if (!kv_pages || !aligned16(kv_pages)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: kv_pages is null or not 16-byte aligned", fn);
+    if (!block_table || !cu_tokens) return fail(h, TETRI_ERR_INVALID_ARG, "%s: null metadata pointer", fn);
+    if (num_reqs < 1 || num_reqs > (1 << 20)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: num_reqs=%d outside 1..%d", fn, num_reqs, 1 << 20);
+    const int64_t most = (int64_t)num_reqs * h->cfg.max_blocks_per_seq * h->cfg.page_size;
+    if (total_tokens < 0 || total_tokens > most)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: total_tokens=%lld outside 0..%lld (num_reqs block-table rows)", fn,
+                    (long long)total_tokens, (long long)most);
+    if (total_tokens == 0) return TETRI_OK;
+    if (!buf || !aligned16(buf)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: buf is null or not 16-byte aligned", fn);
+    const int64_t tiles = total_tokens / 64 + num_reqs;     // >= sum of ceil(n_r / 64)
+    if (tiles > 0x7fffffff) return fail(h, TETRI_ERR_INVALID_ARG, "%s: too many tokens for one launch", fn);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: the handle was created on device %d, the current device is %d", fn, h->device, dev);
+    TransferParams p;
+    p.pool = static_cast<uint16_t *>(kv_pages);
+    p.buf = static_cast<uint16_t *>(buf);
+    p.bt = block_table; p.cu = cu_tokens; p.first = first_tokens;
+    p.R = num_reqs; p.Hkv = h->cfg.num_kv_heads; p.max_blocks = h->cfg.max_blocks_per_seq;
+    // enough workgroups to keep eight per compute unit busy; beyond that a workgroup takes several slabs
+    // and amortises its page lookups over them
+    const int64_t slabs = 2 * (int64_t)p.Hkv;
+    const int64_t want = 8 * (int64_t)std::max(h->num_cus, 1);
+    p.slabs_per_wg = (int32_t)std::min<int64_t>(slabs, std::max<int64_t>(1, tiles * slabs / want));
+    hipError_t e = tetri_launch_kv_transfer(h, p, (int32_t)tiles, to_pool, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
+    return TETRI_OK;
+}
+
+tetri_status tetri_kv_export(tetri_ctx *h, const void *kv_pages, const int32_t *block_table, const int32_t *cu_tokens,
+                             const int32_t *first_tokens, int32_t num_reqs, int64_t total_tokens, void *buf, void *stream)
+{
+    return kv_transfer("tetri_kv_export", h, const_cast<void *>(kv_pages), buf, block_table, cu_tokens, first_tokens,
+                       num_reqs, total_tokens, false, stream);
+}
+
+tetri_status tetri_kv_import(tetri_ctx *h, const void *buf, const int32_t *block_table, const int32_t *cu_tokens,
+                             const int32_t *first_tokens, int32_t num_reqs, int64_t total_tokens, void *kv_pages, void *stream)
+{
+    return kv_transfer("tetri_kv_import", h, kv_pages, const_cast<void *>(buf), block_table, cu_tokens, first_tokens,
+                       num_reqs, total_tokens, true, stream);
+}
+
 static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
                                 const void *kv_pages, void *kv_pages_w, const int32_t *block_table, const int32_t *cu,
                                 const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)

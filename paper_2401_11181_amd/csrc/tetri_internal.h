@@ -57,6 +57,17 @@ struct AppendParams {
     int32_t S, Hkv, D, max_blocks;
 };
 
+// Launch parameters of the KV export / import kernels.
+struct TransferParams {
+    uint16_t *pool;       // the paged pool (read by export, written by import)
+    uint16_t *buf;        // the dense transfer buffer (written by export, read by import)
+    const int32_t *bt, *cu, *first;   // first may be null: every range starts at token 0
+    int32_t R, Hkv, max_blocks;
+    int32_t slabs_per_wg; // (K / V, head) slabs one workgroup moves
+};
+
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
 hipError_t tetri_launch_attn_split(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
+hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t tiles, bool to_pool,
+                                    hipStream_t stream);
 hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

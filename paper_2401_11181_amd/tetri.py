@@ -73,6 +73,10 @@ def lib():
         L.tetri_chunk_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
         L.tetri_chunk_prefill_attn_append.restype = i32
         L.tetri_chunk_prefill_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+        L.tetri_kv_export.restype = i32
+        L.tetri_kv_export.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
+        L.tetri_kv_import.restype = i32
+        L.tetri_kv_import.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
         L.tetri_validate_chunk.restype = i32
         L.tetri_validate_chunk.argtypes = [vp, vp, vp, vp, i32, vp]
         L.tetri_set_option.restype = i32
@@ -227,6 +231,18 @@ class Tetri:
         self._check(lib().tetri_chunk_prefill_attn_append(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
                                                           _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),
                                                           int(num_segs), float(scale), _ptr(out), _stream(stream)))
+
+    def tetri_kv_export(self, kv_pages, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, buf,
+                        stream=None):
+        self._check(lib().tetri_kv_export(self.h, _ptr(kv_pages), _ptr(block_table), _ptr(cu_tokens),
+                                          _ptr(first_tokens), int(num_reqs), int(total_tokens), _ptr(buf),
+                                          _stream(stream)))
+
+    def tetri_kv_import(self, buf, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, kv_pages,
+                        stream=None):
+        self._check(lib().tetri_kv_import(self.h, _ptr(buf), _ptr(block_table), _ptr(cu_tokens),
+                                          _ptr(first_tokens), int(num_reqs), int(total_tokens), _ptr(kv_pages),
+                                          _stream(stream)))
 
     def tetri_validate_chunk(self, block_table, cu_chunk_q_lens, ctx_lens, num_segs, stream=None):
         self._check(lib().tetri_validate_chunk(self.h, _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),

@@ -207,6 +207,27 @@ def main():
                    "frac": round(app_bytes / (app_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }
 
+    # ---- the step after the hot path: request-level KV export of the whole batch and its import on a
+    # receiver (Sec. 3.3.4), timed like the kernels above; moved bytes = payload read + payload written
+    n_req = len(w.prompt_lens)
+    total_tokens = int(sum(w.prompt_lens))
+    payload = 2 * w.num_kv_heads * w.head_dim * total_tokens * 2
+    if 0 < payload <= (8 << 30):
+        d_bt = torch.from_numpy(np.ascontiguousarray(pipe.req_bt)).to(dev)
+        d_cu = torch.from_numpy(np.concatenate([[0], np.cumsum(w.prompt_lens)]).astype(np.int32)).to(dev)
+        xbuf = torch.zeros(payload // 2, dtype=torch.bfloat16, device=dev)
+        exp_ms = group_time(lambda: pipe.handle.tetri_kv_export(pool, d_bt, d_cu, None, n_req, total_tokens, xbuf))
+        imp_ms = group_time(lambda: pipe.handle.tetri_kv_import(xbuf, d_bt, d_cu, None, n_req, total_tokens, pool))
+        result["kv_transfer"] = {
+            "kernel": "kv_transfer_kernel (request-level, %d request(s), %d tokens)" % (n_req, total_tokens),
+            "payload_bytes": payload, "bound": "hbm", "peak_GBs": PEAK_HBM_GBS,
+            "export_ms": round(exp_ms, 5), "export_GBs": round(2 * payload / (exp_ms * 1e-3) / 1e9, 1),
+            "export_frac": round(2 * payload / (exp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "import_ms": round(imp_ms, 5), "import_GBs": round(2 * payload / (imp_ms * 1e-3) / 1e9, 1),
+            "import_frac": round(2 * payload / (imp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        }
+        del xbuf
+
     # ---- the CPU oracle on the host cores of this machine (reported baseline, not the target)
     if not args.no_cpu_baseline:
         from oracle import tetri_oracle

@@ -270,7 +270,9 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  *                       (default 8, at least 2);
  *   "split_bias_stages" stages left out when the handed-over share of a key range is measured: the extra
  *                       work of a helper workgroup, in stages (default 5, not negative);
- *   "split_share_q8"    the share of the remaining stages that is handed over, in 1/256 (default 85: a third).
+ *   "split_share_q8"    the share of the remaining stages that is handed over, in 1/256 (default 85: a third);
+ *   "transfer_slabs"    (K / V, head) slabs one workgroup of tetri_kv_export / tetri_kv_import moves
+ *                       (default 0: chosen from the size of the transfer).
  * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every setting computes the same
  * function to the same tolerance.
  */

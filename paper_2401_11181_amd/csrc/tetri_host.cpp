@@ -124,6 +124,11 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         ctx->split_bias_stages = value;
         return TETRI_OK;
     }
+    if (std::strcmp(key, "transfer_slabs") == 0) {
+        if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: transfer_slabs=%d (>= 0)", value);
+        ctx->transfer_slabs = value;
+        return TETRI_OK;
+    }
     if (std::strcmp(key, "split_share_q8") == 0) {
         if (value < 1 || value > 128) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_share_q8=%d (1..128)", value);
         ctx->split_share_q8 = value;
@@ -323,7 +328,8 @@ static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, vo
                     (long long)total_tokens, (long long)most);
     if (total_tokens == 0) return TETRI_OK;
     if (!buf || !aligned16(buf)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: buf is null or not 16-byte aligned", fn);
-    const int64_t tiles = total_tokens / 64 + num_reqs;     // >= sum of ceil(n_r / 64)
+    const int64_t tile_tokens = 2048 / h->cfg.head_dim;     // a workgroup's tile: 4 KB per (K / V, head) slab
+    const int64_t tiles = total_tokens / tile_tokens + num_reqs;     // >= sum of ceil(n_r / tile_tokens)
     if (tiles > 0x7fffffff) return fail(h, TETRI_ERR_INVALID_ARG, "%s: too many tokens for one launch", fn);
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
@@ -333,11 +339,13 @@ static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, vo
     p.buf = static_cast<uint16_t *>(buf);
     p.bt = block_table; p.cu = cu_tokens; p.first = first_tokens;
     p.R = num_reqs; p.Hkv = h->cfg.num_kv_heads; p.max_blocks = h->cfg.max_blocks_per_seq;
-    // enough workgroups to keep eight per compute unit busy; beyond that a workgroup takes several slabs
-    // and amortises its page lookups over them
+    // enough workgroups for eight per compute unit (a short transfer is bound by the latency of each
+    // workgroup's look-ups, so it wants them all resident at once); beyond that a workgroup takes several slabs, amortises
+    // its page lookups over them and keeps the next slab's loads in flight behind the current one's stores
     const int64_t slabs = 2 * (int64_t)p.Hkv;
     const int64_t want = 8 * (int64_t)std::max(h->num_cus, 1);
     p.slabs_per_wg = (int32_t)std::min<int64_t>(slabs, std::max<int64_t>(1, tiles * slabs / want));
+    if (h->transfer_slabs > 0) p.slabs_per_wg = (int32_t)std::min<int64_t>(slabs, h->transfer_slabs);
     hipError_t e = tetri_launch_kv_transfer(h, p, (int32_t)tiles, to_pool, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;

@@ -14,6 +14,7 @@ struct tetri_ctx {
     int split_min_stages = 8;   // ... those of at least this many stages
     int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
     int split_share_q8 = 85;    // the share of the remaining stages a tile hands over, in 1/256 (a third)
+    int transfer_slabs = 0;     // (K / V, head) slabs per workgroup of the export / import kernels (0: the library chooses)
     int device = 0;         // the device the handle was created on; its scratch memory lives there
     int num_cus = 0;
     char *scratch = nullptr;        // partial results of split tiles: 2 pieces x scratch_units units

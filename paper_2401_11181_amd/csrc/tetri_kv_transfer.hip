@@ -3,25 +3,27 @@
 // request after request as [2 (K, V)][Hkv][n_r][D]; import scatters such a buffer into the pages of
 // the receiving pool.  Pure 16-byte vector copies, HBM-bound, bit-exact by construction.
 //
-// Work split: a workgroup moves 64 consecutive tokens of one request for a few (K / V, head) slabs.
-// On the pool side 16 consecutive tokens of a slab are one contiguous 16 * D * 2 bytes of a page, on
-// the buffer side the 64 tokens are contiguous, so both sides are touched in whole cache lines.
-// The page of every row is looked up once and reused for all slabs of the workgroup.  The data is
-// used once: loads and stores are non-temporal.
+// Work split: a workgroup moves one tile of consecutive tokens of one request (4 KB per slab: 16 tokens
+// for head dimension 128, 32 for 64) for a run of (K / V, head) slabs; each lane owns 16 bytes of one
+// token and walks the slabs, four loads in flight.  On the pool side 16 consecutive tokens of a slab are
+// one contiguous 16 * D * 2 bytes of a page, on the buffer side the tile is contiguous, so both sides
+// are touched in whole cache lines.  The page of a token is looked up once and reused for all slabs.
+// The data is used once: loads and stores are non-temporal.
 #include "tetri_internal.h"
 
 namespace {
 
 constexpr int kPage = 16;
-constexpr int kTile = 64;      // tokens per workgroup
 constexpr int kThreads = 256;
+constexpr int kTileBytes = kThreads * 16;     // one slab of a tile
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// The request that owns 64-token tile `tile` when the tiles of all requests are numbered request after
-// request (request r has ceil(n_r / 64) of them), and the tile's first token inside the request.
+// The request that owns tile `tile` when the tiles (TILE tokens each) of all requests are numbered request
+// after request (request r has ceil(n_r / TILE) of them), and the tile's first token inside the request.
 // Wavefront-wide: 64 requests per step, prefix sum by shuffles.  Every wavefront computes the same
 // result.  Returns -1 when the grid's upper bound overshoots the real number of tiles.
+template <int TILE>
 __device__ inline int find_request(const int32_t *cu, int R, int tile, int lane, int &j0)
 {
     int base = 0;
@@ -29,7 +31,7 @@ __device__ inline int find_request(const int32_t *cu, int R, int tile, int lane,
         const int r = r0 + lane;
         int n = 0;
         if (r < R) n = cu[r + 1] - cu[r];
-        const int t = (n + kTile - 1) / kTile;
+        const int t = (n + TILE - 1) / TILE;
         int incl = t;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -40,7 +42,7 @@ __device__ inline int find_request(const int32_t *cu, int R, int tile, int lane,
         const unsigned long long hit = __ballot(tile < incl && tile >= incl - t);
         if (hit) {
             const int src = __builtin_ctzll(hit);
-            j0 = (tile - __shfl(incl - t, src)) * kTile;
+            j0 = (tile - __shfl(incl - t, src)) * TILE;
             return r0 + src;
         }
         base = __shfl(incl, 63);
@@ -52,48 +54,51 @@ __device__ inline int find_request(const int32_t *cu, int R, int tile, int lane,
 template <int D, bool TO_POOL>
 __global__ __launch_bounds__(kThreads) void kv_transfer_kernel(TransferParams p)
 {
-    constexpr int LPR = D / 8;                 // lanes that move one row of D bf16
-    constexpr int RPP = kThreads / LPR;        // rows per pass of the workgroup
-    constexpr int PASSES = kTile / RPP;
+    constexpr int LPR = D / 8;                 // lanes that move one token's D bf16 of one slab
+    constexpr int TILE = kThreads / LPR;       // tokens per workgroup
     const int tid = threadIdx.x;
     int j0 = 0;
-    const int r = __builtin_amdgcn_readfirstlane(find_request(p.cu, p.R, blockIdx.x, tid & 63, j0));
+    const int r = __builtin_amdgcn_readfirstlane(find_request<TILE>(p.cu, p.R, blockIdx.x, tid & 63, j0));
     if (r < 0) return;
     j0 = __builtin_amdgcn_readfirstlane(j0);
     const int c0 = p.cu[r];
     const int n = p.cu[r + 1] - c0;
     const int first = p.first ? p.first[r] : 0;
+    const int j = j0 + tid / LPR;
+    if (j >= n) return;                        // no barrier below: lanes past the request's end just leave
     const int col = (tid % LPR) * 8;
     const int slabs = 2 * p.Hkv;
-    const size_t page_elems = (size_t)slabs * kPage * D;
-
-    size_t pool_at[PASSES], buf_at[PASSES];
-    bool ok[PASSES];
-#pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-        const int j = j0 + i * RPP + tid / LPR;
-        ok[i] = j < n;
-        const int pos = first + j;
-        const int page = ok[i] ? p.bt[(size_t)r * p.max_blocks + pos / kPage] : 0;
-        pool_at[i] = (size_t)page * page_elems + (size_t)(pos % kPage) * D + col;
-        buf_at[i] = (size_t)slabs * D * c0 + (size_t)j * D + col;
+    const int pos = first + j;
+    const int page = p.bt[(size_t)r * p.max_blocks + pos / kPage];
+    // slab = kv * Hkv + head in both layouts: from one slab to the next both sides advance by a fixed step
+    const int slab0 = blockIdx.y * p.slabs_per_wg;
+    int left = min(slabs, slab0 + p.slabs_per_wg) - slab0;
+    const size_t pool_step = (size_t)kPage * D, buf_step = (size_t)n * D;
+    uint16_t *in_pool = p.pool + ((size_t)page * slabs + slab0) * pool_step + (size_t)(pos % kPage) * D + col;
+    uint16_t *in_buf = p.buf + (size_t)slabs * D * c0 + slab0 * buf_step + (size_t)j * D + col;
+    const uint16_t *src = TO_POOL ? in_buf : in_pool;
+    uint16_t *dst = TO_POOL ? in_pool : in_buf;
+    const size_t src_step = TO_POOL ? buf_step : pool_step, dst_step = TO_POOL ? pool_step : buf_step;
+    auto ld = [&]() {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        src += src_step;
+        return v;
+    };
+    auto st = [&](u32x4 v) {
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(dst));
+        dst += dst_step;
+    };
+#pragma unroll 1
+    for (; left >= 4; left -= 4) {
+        const u32x4 v0 = ld(), v1 = ld(), v2 = ld(), v3 = ld();
+        st(v0), st(v1), st(v2), st(v3);
     }
-    const int slab_end = min(slabs, ((int)blockIdx.y + 1) * p.slabs_per_wg);
-    for (int slab = blockIdx.y * p.slabs_per_wg; slab < slab_end; ++slab) {
-        const size_t in_pool = (size_t)slab * kPage * D;      // slab = kv * Hkv + head in both layouts
-        const size_t in_buf = (size_t)slab * n * D;
-        u32x4 v[PASSES];
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const uint16_t *src = TO_POOL ? p.buf + buf_at[i] + in_buf : p.pool + pool_at[i] + in_pool;
-            if (ok[i]) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-        }
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            uint16_t *dst = TO_POOL ? p.pool + pool_at[i] + in_pool : p.buf + buf_at[i] + in_buf;
-            if (ok[i]) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4 *>(dst));
-        }
+    if (left >= 2) {
+        const u32x4 v0 = ld(), v1 = ld();
+        st(v0), st(v1);
+        left -= 2;
     }
+    if (left) st(ld());
 }
 
 }  // namespace

@@ -248,6 +248,30 @@ TETRI_API tetri_status tetri_kv_import(tetri_ctx *ctx, const void *buf, const in
                                        int64_t total_tokens, void *kv_pages, void *stream);
 
 /*
+ * One decode iteration of a batch of requests over the paged cache: the decode instance's counterpart
+ * of tetri_chunk_prefill_attn (Sec. 2.1: after prefill, each iteration produces one token whose query
+ * attends to the request's KV cache; Sec. 3.4: the decode instance runs the steps of many requests
+ * as one batch over a paged cache).  For request b with ctx_lens[b] cached tokens and query head h
+ *     out[b][h][:] = sum_{j=0..ctx_b} softmax_j(scale * q[b][h] . K_b[j]) * V_b[j]
+ * where K_b[j], V_b[j] of kv head h / (Hq/Hkv) come from kv_pages through block_table[b] for
+ * j < ctx_lens[b] and from k_new[b] / v_new[b] for j = ctx_lens[b] (the new token attends to itself;
+ * cache it with tetri_kv_append and cu_chunk_q_lens = 0, 1, ..., num_reqs, before or after).  The same
+ * function as tetri_chunk_prefill_attn on a chunk of one-token segments, computed by a kernel made
+ * for it: it reads every cached byte once, for all query heads of a kv head together.
+ * Arithmetic as tetri_chunk_prefill_attn; page slots at positions >= ctx_lens[b] are never read.
+ *   q, out [num_reqs][num_q_heads][head_dim]; k_new, v_new [num_reqs][num_kv_heads][head_dim];
+ *   block_table [num_reqs][max_blocks_per_seq]; ctx_lens [num_reqs] (>= 0): device.
+ *   num_reqs >= 1 (not bound by chunk_size or max_segs_per_chunk); max_ctx_len: host scalar, an upper
+ *   bound of ctx_lens that only sizes the launch (how far the keys of a request are split over
+ *   workgroups when there are few requests); results do not depend on it.
+ * Uses the handle's scratch memory when it splits: launches on one handle must not overlap in time.
+ * Results are deterministic run to run.  TETRI_ERR_UNSUPPORTED for more than 32 query heads per kv head.
+ */
+TETRI_API tetri_status tetri_decode_attn(tetri_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                                         const void *kv_pages, const int32_t *block_table, const int32_t *ctx_lens,
+                                         int32_t num_reqs, int32_t max_ctx_len, float scale, void *out, void *stream);
+
+/*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
  * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
  * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages
@@ -271,6 +295,8 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  *   "split_bias_stages" stages left out when the handed-over share of a key range is measured: the extra
  *                       work of a helper workgroup, in stages (default 5, not negative);
  *   "split_share_q8"    the share of the remaining stages that is handed over, in 1/256 (default 85: a third);
+ *   "decode_parts"      workgroups that share the keys of one (request, kv head) in tetri_decode_attn
+ *                       (default 0: chosen from num_reqs and max_ctx_len);
  *   "transfer_slabs"    (K / V, head) slabs one workgroup of tetri_kv_export / tetri_kv_import moves
  *                       (default 0: chosen from the size of the transfer).
  * Unknown keys or values give TETRI_ERR_INVALID_ARG.  Every setting computes the same

@@ -1,0 +1,275 @@
+// One decode iteration over the paged KV cache for gfx950: the counterpart, on the decode instance, of
+// the chunked-prefill kernel (TetriInfer Sec. 2.1: the decode phase produces one token per iteration
+// and its query attends to the request's cached keys and values; Sec. 3.4: the decode instance batches
+// the steps of many requests over a paged cache).
+//
+// The work is reading every cached K and V byte once: HBM-bound (per request and kv head 4 * D bytes
+// per cached token against 4 * D * g flops).  Design:
+//   * a workgroup of four wavefronts owns one (request, kv head, key part); the g query heads that
+//     share the kv head are the columns of one matrix product, so K and V are read once for all of them;
+//   * every wavefront walks its own 32-key steps (step s of the part goes to wavefront s % 4) with
+//     no workgroup barrier in the loop: K and V of a step go straight from global memory into the
+//     wavefront's own LDS tiles (16 bytes per lane per instruction, whole 256-byte rows, swizzled so
+//     that the fragment reads are conflict-free), the next step's K is requested as soon as this
+//     step's K fragments are in registers, the same for V: about 16 KB per wavefront are in flight
+//     at any time, two workgroups per compute unit;
+//   * scores and the PV product run on the matrix cores (S^T = K Q^T, O^T += V^T P^T with
+//     32x32x16 bf16 MFMA; only g of the 32 columns are real, which costs nothing on a kernel that
+//     waits for memory), V is transposed on the way out of LDS by ds_read_b64_tr_b16;
+//   * the four wavefronts merge in LDS; when a request's keys are split over several workgroups
+//     (few requests: the split fills the device) the parts go to scratch memory as unnormalised
+//     (O, m, l) and a second small kernel merges them in a fixed order: results are deterministic.
+// Keys past the end of a request's cache are loaded from a row of zeros and masked, so that stale
+// page contents (which may be NaN bit patterns) never reach an MFMA.
+#include "attn_common.h"
+
+namespace {
+
+using namespace tetri_dev;
+
+constexpr int kWaves = 4;
+
+template <int D>
+__device__ __forceinline__ void issue_tile(const char *page_lo, const char *page_hi, const char *new_row, int first_key, int L,
+                                           bool is_v, int lane, uint32_t lds_base)
+{
+    constexpr int ROW = D * 2, NI = D / 16;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int at = i * 1024 + lane * 16;             // where this lane's 16 bytes land in the tile
+        const int r = at / ROW, cpos = (at % ROW) / 16;
+        const int chunk = cpos ^ (is_v ? v_swizzle<D>(r) : k_swizzle<D>(r));
+        const int key = first_key + r;
+        const char *src = (r < kPage ? page_lo : page_hi) + (r % kPage) * ROW;
+        if (key == L) src = new_row;
+        if (key > L) src = reinterpret_cast<const char *>(g_zero_row);
+        dma16(src + chunk * 16, lds_base + i * 1024);
+    }
+}
+
+// grid: num_reqs * Hkv * parts workgroups, part fastest
+template <int D>
+__global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParams p)
+{
+    constexpr int KSTEPS = D / 16, DBLK = D / 32, NI = D / 16;
+    constexpr int ROW = D * 2, TILE_BYTES = 32 * ROW;
+    static_assert(NI == 4 || NI == 8, "wait counts below");
+    __shared__ __attribute__((aligned(1024))) char smem[kWaves * 2 * TILE_BYTES];
+    __shared__ float stat[kWaves][2][32];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    int x = blockIdx.x;
+    const int part = x % p.parts;
+    x /= p.parts;
+    const int kh = x % p.Hkv, b = x / p.Hkv;
+    const int L = ((const const_i32 *)(uintptr_t)p.ctx)[b];
+    const int steps = (L + 32) / 32;                     // 32-key steps over keys 0..L (key L is the new token)
+    const int spp = (steps + p.parts - 1) / p.parts;     // steps per part
+    const int s_begin = part * spp, s_end = min(steps, s_begin + spp);
+    if (s_begin >= s_end) return;                        // fewer steps than parts: the merge kernel skips this part too
+
+    const const_i32 *bt = (const const_i32 *)(uintptr_t)(p.bt + (size_t)b * p.max_blocks);
+    const size_t head_bytes = (size_t)kPage * ROW, page_bytes = 2 * (size_t)p.Hkv * head_bytes;
+    const char *pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * head_bytes;
+    const char *pool_v = pool_k + (size_t)p.Hkv * head_bytes;
+    const char *new_k = reinterpret_cast<const char *>(p.k_new) + ((size_t)b * p.Hkv + kh) * ROW;
+    const char *new_v = reinterpret_cast<const char *>(p.v_new) + ((size_t)b * p.Hkv + kh) * ROW;
+    char *my = smem + wave * (2 * TILE_BYTES);
+    const uint32_t k_lds = lds_address(my), v_lds = k_lds + TILE_BYTES;
+
+    // pages of a step: clamped entries belong to keys past L and are never dereferenced
+    auto page_of = [&](int step, int which) -> size_t {
+        return (size_t)bt[min(2 * step + which, p.max_blocks - 1)] * page_bytes;
+    };
+    auto issue_k = [&](int step) {
+        issue_tile<D>(pool_k + page_of(step, 0), pool_k + page_of(step, 1), new_k, step * 32, L, false, lane, k_lds);
+    };
+    auto issue_v = [&](int step) {
+        issue_tile<D>(pool_v + page_of(step, 0), pool_v + page_of(step, 1), new_v, step * 32, L, true, lane, v_lds);
+    };
+
+    // the first step's K and V are requested before anything else is read
+    int st = s_begin + wave;
+    if (st < s_end) {
+        issue_k(st);
+        issue_v(st);
+    }
+    // Q fragments (B operand of S^T = K Q^T): column l32 is query head kh * g + l32, zero past g
+    bf16x8 qf[KSTEPS];
+    {
+        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)b * p.Hq + (size_t)kh * p.g + min(l32, p.g - 1)) * D);
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) {
+            uint4 v = qp[2 * st + half];
+            if (l32 >= p.g) v = make_uint4(0, 0, 0, 0);
+            qf[st] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+    // fragment addresses inside the wavefront's tiles (the layouts of the chunked-prefill kernel)
+    uint32_t kbase[KSTEPS], vbase[DBLK];
+    {
+        const int blk = lane >> 4, i16 = lane & 15;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) kbase[st] = l32 * ROW + (((2 * st + half) ^ k_swizzle<D>(l32)) << 4);
+        const int rv = 4 * half + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
+            vbase[db] = TILE_BYTES + rv * ROW + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
+        }
+    }
+
+    f32x16 o[DBLK];
+#pragma unroll
+    for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
+    float m = -1e30f, lsum = 0.f;
+    const float c = p.neg ? -p.c : p.c;
+    const float masked = p.neg ? INFINITY : -INFINITY;
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+
+    for (; st < s_end; st += kWaves) {
+        const bool more = st + kWaves < s_end;
+        // K of this step has landed when only the V loads behind it are outstanding
+        wait_vm<NI>();
+        bf16x8 kf[KSTEPS];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(my + kbase[s]));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // fragments are in registers: the tile may be overwritten
+        if (more) issue_k(st + kWaves);
+        f32x16 sc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sc, 0, 0, 0);
+        // accumulator element v is key 32 * st + 8 * (v / 4) + 4 * half + v % 4; keys past L do not exist
+        if (st * 32 + 31 > L) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (st * 32 + (v / 4) * 8 + 4 * half + (v % 4) > L) sc[v] = masked;
+        }
+        float mx = sc[0] * c;
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v] * c);
+        mx = half_swap_max(mx);
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        bf16x8 pf[2];
+        float l_blk = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+            bf16x2 pp;
+            pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], c, -m));
+            pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v + 1], c, -m));
+            l_blk = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_blk, false);
+            pf[v / 8][v % 8] = pp[0];
+            pf[v / 8][v % 8 + 1] = pp[1];
+        }
+        lsum = lsum * alpha + l_blk;
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+        // V of this step: behind it only the next step's K loads
+        if (more) wait_vm<NI>();
+        else wait_vm<0>();
+        s16x8 vf[2 * DBLK];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db) {
+                const char *a = my + vbase[db] + j * (16 * ROW);
+                const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
+                const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * ROW));
+                vf[j * DBLK + db] = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (more) issue_v(st + kWaves);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
+    }
+
+    // ---- the four wavefronts meet in LDS: each writes its unnormalised O (real columns only) into
+    // its own tiles (all its loads have landed, nobody else touches them), m and the row sum beside
+    const float ltot = half_swap_sum(lsum);
+    if (l32 < p.g) {
+        float *mine = reinterpret_cast<float *>(my) + l32 * D;
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 v4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v4[e] = o[db][q4 * 4 + e];
+                *reinterpret_cast<f32x4 *>(mine + 32 * db + 8 * q4 + 4 * half) = v4;
+            }
+        if (half == 0) { stat[wave][0][l32] = m; stat[wave][1][l32] = ltot; }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < p.g * D; idx += kWaves * 64) {
+        const int col = idx / D, d = idx - col * D;
+        float ms = stat[0][0][col];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, stat[w][0][col]);
+        float acc = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float wgt = __builtin_amdgcn_exp2f(stat[w][0][col] - ms);
+            acc = __builtin_fmaf(reinterpret_cast<const float *>(smem + w * (2 * TILE_BYTES))[col * D + d], wgt, acc);
+            l = __builtin_fmaf(stat[w][1][col], wgt, l);
+        }
+        const size_t head = (size_t)b * p.Hq + (size_t)kh * p.g + col;
+        if (p.parts == 1) {
+            p.out[head * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+        } else {
+            float *dst = p.partial + (head * p.parts + part) * (D + 2);
+            dst[d] = acc;
+            if (d == 0) { dst[D] = ms; dst[D + 1] = l; }
+        }
+    }
+}
+
+// grid: num_reqs * Hq workgroups of D threads: merges the parts of one (request, head) in part order
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p)
+{
+    const int b = blockIdx.x / p.Hq, d = threadIdx.x;
+    const int L = p.ctx[b];
+    const int steps = (L + 32) / 32;
+    const int spp = (steps + p.parts - 1) / p.parts;
+    const int used = (steps + spp - 1) / spp;            // parts that had keys
+    const float *src = p.partial + (size_t)blockIdx.x * p.parts * (D + 2);
+    float ms = src[D];
+    for (int q = 1; q < used; ++q) ms = fmaxf(ms, src[q * (D + 2) + D]);
+    float acc = 0.f, l = 0.f;
+    for (int q = 0; q < used; ++q) {
+        const float wgt = __builtin_amdgcn_exp2f(src[q * (D + 2) + D] - ms);
+        acc = __builtin_fmaf(src[q * (D + 2) + d], wgt, acc);
+        l = __builtin_fmaf(src[q * (D + 2) + D + 1], wgt, l);
+    }
+    p.out[(size_t)blockIdx.x * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+}
+
+}  // namespace
+
+hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStream_t stream)
+{
+    const dim3 grid(p.B * p.Hkv * p.parts), block(kWaves * 64);
+    const int d = h->cfg.head_dim;
+    if (d == 128) hipLaunchKernelGGL(decode_attn_kernel<128>, grid, block, 0, stream, p);
+    else if (d == 64) hipLaunchKernelGGL(decode_attn_kernel<64>, grid, block, 0, stream, p);
+    else return hipErrorInvalidValue;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.parts == 1) return e;
+    if (d == 128) hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.B * p.Hq), dim3(128), 0, stream, p);
+    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.B * p.Hq), dim3(64), 0, stream, p);
+    return hipGetLastError();
+}

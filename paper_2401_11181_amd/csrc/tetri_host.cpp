@@ -124,6 +124,11 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         ctx->split_bias_stages = value;
         return TETRI_OK;
     }
+    if (std::strcmp(key, "decode_parts") == 0) {
+        if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: decode_parts=%d (>= 0)", value);
+        ctx->decode_parts = value;
+        return TETRI_OK;
+    }
     if (std::strcmp(key, "transfer_slabs") == 0) {
         if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: transfer_slabs=%d (>= 0)", value);
         ctx->transfer_slabs = value;
@@ -363,6 +368,61 @@ tetri_status tetri_kv_import(tetri_ctx *h, const void *buf, const int32_t *block
 {
     return kv_transfer("tetri_kv_import", h, kv_pages, const_cast<void *>(buf), block_table, cu_tokens, first_tokens,
                        num_reqs, total_tokens, true, stream);
+}
+
+tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                               const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len,
+                               float scale, void *out, void *stream)
+{
+    const char *fn = "tetri_decode_attn";
+    if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
+    const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
+    const char *names[] = {"q", "k_new", "v_new", "kv_pages", "out"};
+    for (int i = 0; i < 5; ++i) {
+        if (!ptrs[i]) return fail(h, TETRI_ERR_INVALID_ARG, "%s: %s is null", fn, names[i]);
+        if (!aligned16(ptrs[i])) return fail(h, TETRI_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", fn, names[i]);
+    }
+    if (!block_table || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "%s: null metadata pointer", fn);
+    if (!std::isfinite(scale)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: scale is not finite", fn);
+    const tetri_config &cfg = h->cfg;
+    if (num_reqs < 1 || (int64_t)num_reqs * cfg.num_kv_heads > (1 << 24))
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: num_reqs=%d outside 1..%d", fn, num_reqs, (1 << 24) / cfg.num_kv_heads);
+    const int64_t most = (int64_t)cfg.max_blocks_per_seq * cfg.page_size;
+    if (max_ctx_len < 0 || max_ctx_len > most)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: max_ctx_len=%d outside 0..%lld", fn, max_ctx_len, (long long)most);
+    if (cfg.num_q_heads / cfg.num_kv_heads > 32)
+        return fail(h, TETRI_ERR_UNSUPPORTED, "%s: more than 32 query heads per kv head", fn);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: the handle was created on device %d, the current device is %d", fn, h->device, dev);
+    DecodeParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.pages = static_cast<const uint16_t *>(kv_pages);
+    p.bt = block_table; p.ctx = ctx_lens;
+    p.out = static_cast<uint16_t *>(out);
+    p.partial = reinterpret_cast<float *>(h->scratch);
+    p.B = num_reqs; p.Hq = cfg.num_q_heads; p.Hkv = cfg.num_kv_heads; p.g = p.Hq / p.Hkv;
+    p.max_blocks = cfg.max_blocks_per_seq;
+    p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
+    p.neg = scale < 0.f;
+    // Few requests: split every request's keys over several workgroups until the device has four
+    // workgroups per compute unit, each with at least eight 32-key steps, as far as the scratch
+    // memory for the parts reaches.
+    const int64_t pairs = (int64_t)num_reqs * p.Hkv;
+    const int64_t steps = ((int64_t)max_ctx_len + 32) / 32;
+    const int64_t per_part = (int64_t)num_reqs * p.Hq * (cfg.head_dim + 2) * 4;        // scratch bytes of one part
+    const int64_t fit = (int64_t)(2 * h->scratch_units * h->unit_bytes) / per_part;
+    int64_t parts = (4 * (int64_t)std::max(h->num_cus, 1) + pairs - 1) / pairs;
+    parts = std::min(parts, std::max<int64_t>(1, steps / 8));
+    if (h->decode_parts > 0) parts = h->decode_parts;
+    parts = std::max<int64_t>(1, std::min(parts, std::min<int64_t>(fit, 4096)));
+    p.parts = (int32_t)parts;
+    if (pairs * parts > 0x7fffffff) return fail(h, TETRI_ERR_INVALID_ARG, "%s: too many workgroups", fn);
+    hipError_t e = tetri_launch_decode(h, p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
+    return TETRI_OK;
 }
 
 static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,

@@ -14,6 +14,7 @@ struct tetri_ctx {
     int split_min_stages = 8;   // ... those of at least this many stages
     int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
     int split_share_q8 = 85;    // the share of the remaining stages a tile hands over, in 1/256 (a third)
+    int decode_parts = 0;       // key parts per (request, kv head) of the decode kernel (0: the library chooses)
     int transfer_slabs = 0;     // (K / V, head) slabs per workgroup of the export / import kernels (0: the library chooses)
     int device = 0;         // the device the handle was created on; its scratch memory lives there
     int num_cus = 0;
@@ -67,8 +68,21 @@ struct TransferParams {
     int32_t slabs_per_wg; // (K / V, head) slabs one workgroup moves
 };
 
+// Launch parameters of the decode-iteration kernels.
+struct DecodeParams {
+    const uint16_t *q, *k_new, *v_new, *pages;
+    const int32_t *bt, *ctx;
+    uint16_t *out;
+    float *partial;       // scratch: [(request * Hq + head) * parts + part][D + 2] = unnormalised O, m, l
+    int32_t B, Hq, Hkv, g, max_blocks;
+    int32_t parts;        // workgroups that share one (request, kv head)'s keys
+    float c;              // |scale| * log2(e)
+    int32_t neg;          // 1 if scale < 0
+};
+
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
 hipError_t tetri_launch_attn_split(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
 hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t tiles, bool to_pool,
                                     hipStream_t stream);
+hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStream_t stream);
 hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

@@ -228,6 +228,34 @@ def main():
         }
         del xbuf
 
+    # ---- the decode instance's counterpart (Sec. 3.4): one decode iteration of 64 requests with 2048
+    # cached tokens each, same head shape, scattered pages; bytes = the cached K and V, read once
+    dB, dctx = 64, 2048
+    d_need = -(-(dctx + 1) // w.page_size)
+    kv_bytes = dB * dctx * 2 * w.num_kv_heads * w.head_dim * 2
+    if kv_bytes <= (16 << 30):
+        dh = tetri.Tetri(w.num_q_heads, w.num_kv_heads, w.head_dim, 64, dB * d_need, d_need, 8)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        dpool = (torch.randn((dB * d_need, 2, w.num_kv_heads, w.page_size, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        dq = (torch.randn((dB, w.num_q_heads, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        dk = (torch.randn((dB, w.num_kv_heads, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        dv = torch.randn(dk.shape, device=dev, generator=gen).to(torch.bfloat16)
+        dout = torch.zeros_like(dq)
+        dbt = torch.from_numpy(np.random.default_rng(w.seed).permutation(dB * d_need).astype(np.int32).reshape(dB, d_need)).to(dev)
+        dcl = torch.full((dB,), dctx, dtype=torch.int32, device=dev)
+        dec_ms = group_time(lambda: dh.tetri_decode_attn(dq, dk, dv, dpool, dbt, dcl, dB, dctx, w.scale, dout))
+        result["decode"] = {
+            "kernel": "decode_attn_kernel (%d requests x %d cached tokens, %dx%d query heads, %d kv heads)" % (
+                dB, dctx, w.num_q_heads, w.head_dim, w.num_kv_heads),
+            "bound": "hbm", "kv_bytes": kv_bytes, "ms": round(dec_ms, 5),
+            "achieved_GBs": round(kv_bytes / (dec_ms * 1e-3) / 1e9, 1), "peak_GBs": PEAK_HBM_GBS,
+            "frac": round(kv_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "tokens_per_s": round(dB / (dec_ms * 1e-3), 1),
+        }
+        dh.close()
+        del dpool
+
     # ---- the CPU oracle on the host cores of this machine (reported baseline, not the target)
     if not args.no_cpu_baseline:
         from oracle import tetri_oracle

@@ -28,6 +28,7 @@ namespace {
 using namespace tetri_dev;
 
 constexpr int kWaves = 4;
+constexpr int kMaxParts = 1024;   // most workgroups one (request, kv head)'s keys are split over
 
 template <int D>
 __device__ __forceinline__ void issue_tile(const char *page_lo, const char *page_hi, const char *new_row, int first_key, int L,
@@ -237,25 +238,51 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
     }
 }
 
-// grid: num_reqs * Hq workgroups of D threads: merges the parts of one (request, head) in part order
+// grid: num_reqs * Hq workgroups: merges the parts of one (request, head).  The parts' weights are
+// computed once (one part per thread), then thread (group, d) sums every (256 / D)-th part of element
+// d with several loads in flight and the groups are added in a fixed order: deterministic.
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p)
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p)
 {
-    const int b = blockIdx.x / p.Hq, d = threadIdx.x;
+    constexpr int G = 256 / D;
+    __shared__ float w[kMaxParts];
+    __shared__ float red[2][4];
+    __shared__ float sums[G][D];
+    const int b = blockIdx.x / p.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = p.ctx[b];
     const int steps = (L + 32) / 32;
     const int spp = (steps + p.parts - 1) / p.parts;
     const int used = (steps + spp - 1) / spp;            // parts that had keys
     const float *src = p.partial + (size_t)blockIdx.x * p.parts * (D + 2);
-    float ms = src[D];
-    for (int q = 1; q < used; ++q) ms = fmaxf(ms, src[q * (D + 2) + D]);
-    float acc = 0.f, l = 0.f;
-    for (int q = 0; q < used; ++q) {
-        const float wgt = __builtin_amdgcn_exp2f(src[q * (D + 2) + D] - ms);
-        acc = __builtin_fmaf(src[q * (D + 2) + d], wgt, acc);
-        l = __builtin_fmaf(src[q * (D + 2) + D + 1], wgt, l);
+    float ms = -INFINITY;
+    for (int q = tid; q < used; q += 256) ms = fmaxf(ms, src[q * (D + 2) + D]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) ms = fmaxf(ms, __shfl_xor(ms, d));
+    if (lane == 0) red[0][wave] = ms;
+    __syncthreads();
+    ms = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    float l = 0.f;
+    for (int q = tid; q < used; q += 256) {
+        const float wq = __builtin_amdgcn_exp2f(src[q * (D + 2) + D] - ms);
+        w[q] = wq;
+        l = __builtin_fmaf(src[q * (D + 2) + D + 1], wq, l);
     }
-    p.out[(size_t)blockIdx.x * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) l += __shfl_xor(l, d);
+    if (lane == 0) red[1][wave] = l;
+    __syncthreads();
+    l = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    const int grp = tid / D, d = tid - grp * D;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int q = grp; q < used; q += G) acc = __builtin_fmaf(src[q * (D + 2) + d], w[q], acc);
+    sums[grp][d] = acc;
+    __syncthreads();
+    if (grp == 0) {
+#pragma unroll
+        for (int g = 1; g < G; ++g) acc += sums[g][d];
+        p.out[(size_t)blockIdx.x * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+    }
 }
 
 }  // namespace
@@ -269,7 +296,8 @@ hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStr
     else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.parts == 1) return e;
-    if (d == 128) hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.B * p.Hq), dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.B * p.Hq), dim3(64), 0, stream, p);
+    if (p.parts > kMaxParts) return hipErrorInvalidValue;
+    if (d == 128) hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(p.B * p.Hq), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(p.B * p.Hq), dim3(256), 0, stream, p);
     return hipGetLastError();
 }

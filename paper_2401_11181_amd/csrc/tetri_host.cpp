@@ -417,7 +417,7 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
     int64_t parts = (4 * (int64_t)std::max(h->num_cus, 1) + pairs - 1) / pairs;
     parts = std::min(parts, std::max<int64_t>(1, steps / 8));
     if (h->decode_parts > 0) parts = h->decode_parts;
-    parts = std::max<int64_t>(1, std::min(parts, std::min<int64_t>(fit, 4096)));
+    parts = std::max<int64_t>(1, std::min(parts, std::min<int64_t>(fit, 1024)));
     p.parts = (int32_t)parts;
     if (pairs * parts > 0x7fffffff) return fail(h, TETRI_ERR_INVALID_ARG, "%s: too many workgroups", fn);
     hipError_t e = tetri_launch_decode(h, p, static_cast<hipStream_t>(stream));

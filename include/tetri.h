@@ -272,6 +272,19 @@ TETRI_API tetri_status tetri_decode_attn(tetri_ctx *ctx, const void *q, const vo
                                          int32_t num_reqs, int32_t max_ctx_len, float scale, void *out, void *stream);
 
 /*
+ * The decode iteration and the caching of its new tokens in ONE launch (Sec. 2.1: every decode
+ * iteration extends the KV cache by one token).  Same `out`, bit for bit, as tetri_decode_attn, and the
+ * same pool as tetri_kv_append with cu_chunk_q_lens = 0, 1, ..., num_reqs afterwards: k_new[b] / v_new[b]
+ * are written to slot ctx_lens[b] % page_size of page block_table[b][ctx_lens[b] / page_size], and
+ * nothing else is written.  block_table must therefore cover position ctx_lens[b]
+ * (max_ctx_len <= max_blocks_per_seq * page_size - 1).  Arguments as tetri_decode_attn, kv_pages in/out.
+ */
+TETRI_API tetri_status tetri_decode_attn_append(tetri_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                                                void *kv_pages, const int32_t *block_table, const int32_t *ctx_lens,
+                                                int32_t num_reqs, int32_t max_ctx_len, float scale, void *out,
+                                                void *stream);
+
+/*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
  * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
  * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages

@@ -97,6 +97,16 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
         issue_k(st);
         issue_v(st);
     }
+    // Fused append: the workgroup whose part ends with key L caches the new token's K and V row of
+    // this kv head in slot L % 16 of page block_table[b][L / 16] (16 bytes per lane; nothing in this
+    // launch reads that slot: every wavefront takes key L from k_new / v_new).
+    if (p.pages_w != nullptr && s_end == steps && wave == kWaves - 1 && lane < 2 * (ROW / 16)) {
+        const int which = lane / (ROW / 16), chunk = lane % (ROW / 16);
+        const size_t at = (size_t)bt[L / kPage] * page_bytes + ((size_t)which * p.Hkv + kh) * head_bytes
+                          + (size_t)(L % kPage) * ROW + chunk * 16;
+        const uint4 v = *reinterpret_cast<const uint4 *>((which ? new_v : new_k) + chunk * 16);
+        *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(p.pages_w) + at) = v;
+    }
     // Q fragments (B operand of S^T = K Q^T): column l32 is query head kh * g + l32, zero past g
     bf16x8 qf[KSTEPS];
     {

@@ -370,11 +370,11 @@ tetri_status tetri_kv_import(tetri_ctx *h, const void *buf, const int32_t *block
                        num_reqs, total_tokens, true, stream);
 }
 
-tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, const void *kv_pages,
-                               const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len,
-                               float scale, void *out, void *stream)
+static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                  const void *kv_pages, void *kv_pages_w, const int32_t *block_table,
+                                  const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len, float scale, void *out,
+                                  void *stream)
 {
-    const char *fn = "tetri_decode_attn";
     if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
     const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
     const char *names[] = {"q", "k_new", "v_new", "kv_pages", "out"};
@@ -387,7 +387,8 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
     const tetri_config &cfg = h->cfg;
     if (num_reqs < 1 || (int64_t)num_reqs * cfg.num_kv_heads > (1 << 24))
         return fail(h, TETRI_ERR_INVALID_ARG, "%s: num_reqs=%d outside 1..%d", fn, num_reqs, (1 << 24) / cfg.num_kv_heads);
-    const int64_t most = (int64_t)cfg.max_blocks_per_seq * cfg.page_size;
+    // with the fused append the new token itself needs a slot
+    const int64_t most = (int64_t)cfg.max_blocks_per_seq * cfg.page_size - (kv_pages_w ? 1 : 0);
     if (max_ctx_len < 0 || max_ctx_len > most)
         return fail(h, TETRI_ERR_INVALID_ARG, "%s: max_ctx_len=%d outside 0..%lld", fn, max_ctx_len, (long long)most);
     if (cfg.num_q_heads / cfg.num_kv_heads > 32)
@@ -402,6 +403,7 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
     p.pages = static_cast<const uint16_t *>(kv_pages);
     p.bt = block_table; p.ctx = ctx_lens;
     p.out = static_cast<uint16_t *>(out);
+    p.pages_w = static_cast<uint16_t *>(kv_pages_w);
     p.partial = reinterpret_cast<float *>(h->scratch);
     p.B = num_reqs; p.Hq = cfg.num_q_heads; p.Hkv = cfg.num_kv_heads; p.g = p.Hq / p.Hkv;
     p.max_blocks = cfg.max_blocks_per_seq;
@@ -423,6 +425,22 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
     hipError_t e = tetri_launch_decode(h, p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;
+}
+
+tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                               const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len,
+                               float scale, void *out, void *stream)
+{
+    return decode_common("tetri_decode_attn", h, q, k_new, v_new, kv_pages, nullptr, block_table, ctx_lens, num_reqs,
+                         max_ctx_len, scale, out, stream);
+}
+
+tetri_status tetri_decode_attn_append(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, void *kv_pages,
+                                      const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs,
+                                      int32_t max_ctx_len, float scale, void *out, void *stream)
+{
+    return decode_common("tetri_decode_attn_append", h, q, k_new, v_new, kv_pages, kv_pages, block_table, ctx_lens,
+                         num_reqs, max_ctx_len, scale, out, stream);
 }
 
 static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,

@@ -73,6 +73,7 @@ struct DecodeParams {
     const uint16_t *q, *k_new, *v_new, *pages;
     const int32_t *bt, *ctx;
     uint16_t *out;
+    uint16_t *pages_w;    // pool for the fused append of the new token (null: no append)
     float *partial;       // scratch: [(request * Hq + head) * parts + part][D + 2] = unnormalised O, m, l
     int32_t B, Hq, Hkv, g, max_blocks;
     int32_t parts;        // workgroups that share one (request, kv head)'s keys

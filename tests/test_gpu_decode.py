@@ -177,3 +177,76 @@ def test_opt13b_heads_batch():
     sharp = synth.sharp(w)
     args = build(sharp)
     print(gc.compare([run_gpu(sharp, *args)], [reference(sharp, *args)], label="opt13b-decode-sharp"))
+
+
+@pytest.mark.parametrize("name,parts", [("ragged-mha", 0), ("gqa4", 3), ("gqa3-d64", 0), ("mha-d64", 2), ("gqa32", 1)])
+def test_fused_decode_append_equals_two_calls(name, parts):
+    """tetri_decode_attn_append == tetri_decode_attn then tetri_kv_append (cu = 0..B), bit for bit, and the
+    pool equals the numpy placement of the new tokens."""
+    lens, hq, hkv, d = CASES[name]
+    w = synth.small("decf-" + name, lens, 64, hq, hkv, d, seed=340)
+    q, k, v, pool, bt, ctx = build(w)
+    B = len(ctx)
+    h = tetri.Tetri(hq, hkv, d, max(B, 16), w.num_pages, bt.shape[1], max(B, 8))
+    if parts:
+        h.tetri_set_option("decode_parts", parts)
+    dq, dk, dv = q.to(DEV), k.to(DEV), v.to(DEV)
+    dbt, dctx = torch.from_numpy(bt).to(DEV), torch.from_numpy(ctx).to(DEV)
+    pool_a, pool_b = pool.to(DEV), pool.to(DEV)
+    out_a = torch.zeros_like(dq)
+    out_b = torch.zeros_like(dq)
+    h.tetri_decode_attn(dq, dk, dv, pool_a, dbt, dctx, B, int(ctx.max()), w.scale, out_a)
+    kpad = torch.zeros((max(B, 16), hkv, d), dtype=torch.bfloat16, device=DEV)
+    vpad = torch.zeros_like(kpad)
+    kpad[:B], vpad[:B] = dk, dv
+    h.tetri_kv_append(kpad, vpad, pool_a, dbt, torch.arange(B + 1, dtype=torch.int32, device=DEV), dctx, B)
+    h.tetri_decode_attn_append(dq, dk, dv, pool_b, dbt, dctx, B, int(ctx.max()), w.scale, out_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16))
+    assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
+    want = pool.clone()
+    for b in range(B):
+        L = int(ctx[b])
+        want[bt[b, L // 16], 0, :, L % 16, :] = k[b]
+        want[bt[b, L // 16], 1, :, L % 16, :] = v[b]
+    assert torch.equal(pool_b.cpu().view(torch.int16), want.view(torch.int16))
+    h.close()
+
+
+def test_decode_loop_extends_the_cache(oracle):
+    """Prefill a prompt's first tokens with the chunked-prefill path, then decode the rest token by token
+    with the fused call: every decode output equals that row of the one-shot oracle prefill, and the
+    final pool equals the oracle's."""
+    w = synth.small("dec-loop", [75, 41], 32, 4, 2, 128, seed=341)
+    qs, ks, vs, tables = gc.workload_tensors(w)
+    ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
+    n_dec = 9
+    short = synth.small("dec-loop", [n - n_dec for n in w.prompt_lens], 32, 4, 2, 128, seed=341)
+    short.num_pages = w.num_pages
+    cut = lambda ts: [t[:n - n_dec] for t, n in zip(ts, w.prompt_lens)]
+    _, pool, _, _ = gc.gpu_prefill(short, cut(qs), cut(ks), cut(vs), tables, fused=True)
+    B = len(w.prompt_lens)
+    mb = max(len(t) for t in tables)
+    bt = np.zeros((B, mb), dtype=np.int32)
+    for r, t in enumerate(tables):
+        bt[r, :len(t)] = t
+    h = tetri.Tetri(w.num_q_heads, w.num_kv_heads, w.head_dim, 64, w.num_pages, mb, 8)
+    dbt = torch.from_numpy(bt).to(DEV)
+    outs = [[] for _ in range(B)]
+    for step in range(n_dec):
+        pos = [n - n_dec + step for n in w.prompt_lens]
+        dq = torch.stack([qs[r][pos[r]] for r in range(B)]).to(DEV)
+        dk = torch.stack([ks[r][pos[r]] for r in range(B)]).to(DEV)
+        dv = torch.stack([vs[r][pos[r]] for r in range(B)]).to(DEV)
+        out = torch.zeros_like(dq)
+        h.tetri_decode_attn_append(dq, dk, dv, pool, dbt, torch.tensor(pos, dtype=torch.int32, device=DEV), B,
+                                   max(pos), w.scale, out)
+        torch.cuda.synchronize()
+        for r in range(B):
+            outs[r].append(out[r].cpu())
+    got = [torch.stack(o) for o in outs]
+    want = [ref[r][n - n_dec:] for r, n in enumerate(w.prompt_lens)]
+    print(gc.compare(got, want, label="decode-loop"))
+    bits = gc.oracle_pool_bits(oracle, w, ks, vs, tables)
+    assert np.array_equal(pool.cpu().view(torch.int16).numpy().view(np.uint16), bits)
+    h.close()

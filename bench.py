@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--policy", default=None, choices=["fcfs", "sjf", "ljf"],
                     help="order the workload's requests with tetri_schedule (Sec. 3.3.2) before packing")
     ap.add_argument("--sched-batch", type=int, default=0, help="PrefillSchedBatch: requests per sorted group (0: all)")
+    ap.add_argument("--export", default=None, choices=["request", "chunk"],
+                    help="add the KV export to the step: after the last chunk (request-level) or per chunk on a second "
+                         "stream while the next chunk is prefilled (chunk-level), Sec. 3.3.4")
     ap.add_argument("--chunk-size", type=int, default=None, help="ChunkSize override (the saturation sweep of Sec. 2.2)")
     ap.add_argument("--prompt-len", type=int, default=None, help="replace the workload's prompts by one prompt of this length")
     args = ap.parse_args()
@@ -74,7 +77,7 @@ def main():
     tables = synth.place_pages(w)
     pipe = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                            w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
-                           use_graph=(args.mode == "graph"), fused=not args.two_launches)
+                           use_graph=(args.mode == "graph"), fused=not args.two_launches, export=args.export)
     if args.variant is not None:
         pipe.handle.tetri_set_option("attn_variant", args.variant)
     nC, C = pipe.n_chunks, w.chunk_size
@@ -182,7 +185,7 @@ def main():
                         "page size %d, causal, seed %d" % (w.name, len(w.prompt_lens), sum(w.prompt_lens), nC, C,
                                                            w.num_q_heads, w.head_dim, w.num_kv_heads, w.page_size,
                                                            w.seed),
-            "chunk_size": C, "launch_mode": args.mode,
+            "chunk_size": C, "launch_mode": args.mode, "kv_export_in_step": args.export,
             "segments_per_chunk": {"mean": round(float(np.mean([len(pipe.chunk_segments(c)) for c in range(nC)])), 2),
                                    "max": int(max(len(pipe.chunk_segments(c)) for c in range(nC)))},
             "step": "pack + metadata + upload + per chunk " +

@@ -236,6 +236,9 @@ TETRI_API tetri_status tetri_chunk_prefill_attn_append(tetri_ctx *ctx, const voi
  *   cu_tokens [num_reqs + 1] (cu_tokens[0] = 0, non-decreasing), first_tokens [num_reqs] or NULL: device, in.
  *   num_reqs: host scalar >= 1.  total_tokens: host scalar, must equal cu_tokens[num_reqs]
  *   (it sizes the launch; 0 is allowed and launches nothing).
+ * Neither call uses the handle's scratch memory: they may overlap other launches of the same handle on
+ * another stream (chunk-level export while the next chunk is prefilled), as long as the host calls
+ * themselves come from one thread at a time.
  * Token ranges of one import must not overlap in the pool.  The device arrays are trusted like those of
  * the other launching calls.  TETRI_ERR_INVALID_ARG for null / misaligned pointers and counts out of
  * range (total_tokens above num_reqs * max_blocks_per_seq * page_size).

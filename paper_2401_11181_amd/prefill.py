@@ -112,11 +112,19 @@ class PrefillPipeline:
     RING = 4    # pinned staging buffers in flight
 
     def __init__(self, prompt_lens, order, chunk_size, num_q_heads, num_kv_heads, head_dim, num_pages,
-                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False, fused=True):
+                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False, fused=True, export=None):
         self.device = torch.device(device)
         self.C, self.Hq, self.Hkv, self.D = chunk_size, num_q_heads, num_kv_heads, head_dim
         self.scale = float(scale)
         self.fused = fused          # one launch per chunk (attention + append) instead of two
+        # KV transfer granularity of the step (Sec. 3.3.4): None = no export, "request" = one export of every
+        # request after the last chunk, "chunk" = each chunk's slice exported on a second stream while the next
+        # chunk is prefilled
+        self.export = export
+        if export not in (None, "request", "chunk"):
+            raise ValueError("export must be None, 'request' or 'chunk'")
+        if export and use_graph:
+            raise ValueError("the export modes are launched eagerly")
         self.lens = np.ascontiguousarray(prompt_lens, dtype=np.int32)
         self.order = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
         self.max_blocks = max(1, max(len(t) for t in req_block_tables))
@@ -146,6 +154,30 @@ class PrefillPipeline:
         self.q, self.k, self.v, self.pool, self.out = q_chunks, k_chunks, v_chunks, kv_pages, out_chunks
         self.graph = None
         self._bind_args()
+        if self.export:
+            total = int(self.lens.sum())
+            self.xbuf = torch.zeros(2 * self.Hkv * self.D * max(total, 1), dtype=self.pool.dtype, device=self.device)
+            self.req_bt_dev = torch.from_numpy(self.req_bt).to(self.device)
+            self.req_cu_dev = torch.from_numpy(np.concatenate([[0], np.cumsum(self.lens)]).astype(np.int32)).to(self.device)
+            self.side = torch.cuda.Stream(device=self.device)      # default priority
+            self.chunk_done = [torch.cuda.Event() for _ in range(self.n_chunks)]
+            self.side_done = torch.cuda.Event()
+            # a chunk's slice goes behind the slices of the chunks before it
+            self.chunk_tokens = [sum(n for _r, _s, n in self.chunk_segments(c)) for c in range(self.n_chunks)]
+            self.chunk_at = [2 * self.Hkv * self.D * sum(self.chunk_tokens[:c]) for c in range(self.n_chunks)]
+            import ctypes
+            vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+            base, esz = self.meta_dev.data_ptr(), self.xbuf.element_size()
+            self._side_stream = vp(self.side.cuda_stream)
+            self._chunk_export_args = []
+            for c in range(self.n_chunks):
+                o_cu, o_ctx, o_bt, S = self.layout[c]
+                self._chunk_export_args.append((self.handle.h, vp(self.pool.data_ptr()), vp(base + 4 * o_bt), vp(base + 4 * o_cu),
+                                                vp(base + 4 * o_ctx), i32(S), i64(self.chunk_tokens[c]),
+                                                vp(self.xbuf.data_ptr() + esz * self.chunk_at[c]), self._side_stream))
+            self._request_export_args = (self.handle.h, vp(self.pool.data_ptr()), vp(self.req_bt_dev.data_ptr()),
+                                         vp(self.req_cu_dev.data_ptr()), None, i32(len(self.lens)), i64(total),
+                                         vp(self.xbuf.data_ptr()))
 
     # --- host part of a step --------------------------------------------------------------------
     def host_plan(self, slot):
@@ -195,6 +227,20 @@ class PrefillPipeline:
             else:
                 self.launch_attn(c, stream)
                 self.launch_append(c, stream)
+            if self.export == "chunk":
+                # the slice this chunk cached, named by the chunk's own metadata arrays
+                self.chunk_done[c].record()
+                self.side.wait_event(self.chunk_done[c])
+                rc = self._lib.tetri_kv_export(*self._chunk_export_args[c])
+                if rc != tetri.TETRI_OK:
+                    raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
+        if self.export == "chunk":
+            self.side_done.record(self.side)
+            torch.cuda.current_stream().wait_event(self.side_done)
+        elif self.export == "request":
+            rc = self._lib.tetri_kv_export(*self._request_export_args, stream)
+            if rc != tetri.TETRI_OK:
+                raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
 
     def step(self):
         slot = self.turn % self.RING

@@ -26,6 +26,60 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {("opt13b", "fused"): 76.3e6}
 
 
+def layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev):
+    """Throughput and latency of one OPT-13B-shaped decoder layer's prefill against the prompt length C
+    (one chunk, empty cache): where throughput goes flat is the accelerator-saturate threshold that
+    Sec. 2.2 / Sec. 3.3.3 take as ChunkSize.  The attention is this library's fused launch; the four
+    projections (QKV 5120x15360, out 5120x5120, MLP 5120x20480 and back) are library GEMMs through
+    torch.matmul, here only as the context the paper's experiment needs."""
+    hidden, heads, d = 5120, 40, 128
+    shapes = [(hidden, 3 * hidden), (hidden, hidden), (hidden, 4 * hidden), (4 * hidden, hidden)]
+    weights = [(torch.randn(k, n, device=dev) * 0.02).to(torch.bfloat16) for k, n in shapes]
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    for C in (128, 256, 512, 1024, 2048, 4096, 8192):
+        w = dataclasses.replace(synth.workload("opt13b"), prompt_lens=[C], order=[0], chunk_size=C,
+                                num_pages=C // 16 + 8)
+        pipe = PrefillPipeline(w.prompt_lens, w.order, C, heads, heads, d, w.num_pages, synth.place_pages(w), w.scale,
+                               device=dev)
+        q = (torch.randn((1, C, heads, d), device=dev) * w.std).to(torch.bfloat16)
+        k = (torch.randn((1, C, heads, d), device=dev) * w.std).to(torch.bfloat16)
+        v = torch.randn_like(k)
+        out = torch.zeros_like(q)
+        pool = synth.pool_sentinel((w.num_pages, 2, heads, 16, d), device=dev)
+        pipe.bind(q, k, v, pool, out)
+        pipe.step()
+        torch.cuda.synchronize()
+        attn_ms = timed(lambda: pipe.launch_fused(0))
+        x = [(torch.randn(C, kdim, device=dev) * 0.02).to(torch.bfloat16) for kdim, _n in shapes]
+        gemm_ms = sum(timed(lambda i=i: torch.matmul(x[i], weights[i])) for i in range(4))
+        attn_flops = pipe.flops(0)
+        gemm_flops = sum(2.0 * C * kdim * n for kdim, n in shapes)
+        rows.append({"C": C, "attn_ms": round(attn_ms, 5), "gemm_ms": round(gemm_ms, 5),
+                     "layer_ms": round(attn_ms + gemm_ms, 5),
+                     "attn_tflops": round(attn_flops / attn_ms / 1e9, 1), "gemm_tflops": round(gemm_flops / gemm_ms / 1e9, 1),
+                     "layer_tflops": round((attn_flops + gemm_flops) / (attn_ms + gemm_ms) / 1e9, 1),
+                     "tokens_per_ms": round(C / (attn_ms + gemm_ms), 1)})
+        del pipe, pool
+    print(json.dumps({"metric": "layer_prefill_saturation_sweep", "unit": "TFLOP/s", "data": "synthetic",
+                      "config": {"workload": "one OPT-13B-shaped decoder layer (hidden 5120, 40x128 heads), one prompt of C tokens, "
+                                             "empty cache, bf16; attention = this library, projections = library GEMMs"},
+                      "rows": rows}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +99,10 @@ def main():
     ap.add_argument("--export", default=None, choices=["request", "chunk"],
                     help="add the KV export to the step: after the last chunk (request-level) or per chunk on a second "
                          "stream while the next chunk is prefilled (chunk-level), Sec. 3.3.4")
+    ap.add_argument("--layer-sweep", action="store_true",
+                    help="instead of the benchmark: the paper's saturation experiment (Sec. 2.2) for one 13B-shaped "
+                         "decoder layer: this library's attention of a C-token prompt plus the layer's four projections "
+                         "as plain library GEMMs, for C = 128 .. 8192")
     ap.add_argument("--chunk-size", type=int, default=None, help="ChunkSize override (the saturation sweep of Sec. 2.2)")
     ap.add_argument("--prompt-len", type=int, default=None, help="replace the workload's prompts by one prompt of this length")
     args = ap.parse_args()
@@ -64,6 +122,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.layer_sweep:
+        return layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev)
     w = synth.workload(args.workload)
     if args.prompt_len is not None:
         w = dataclasses.replace(w, name=w.name + "-len%d" % args.prompt_len, prompt_lens=[args.prompt_len], order=[0],

@@ -8,6 +8,13 @@ host chunk packing + per-chunk metadata, one metadata upload, then for every chu
 attention launch and one KV-append launch (TetriInfer Sec. 3.3.3: prefill one ChunkSize chunk at
 a time).  Q/K/V of every chunk and the page pool are resident in HBM before the timed region.
 Prints ONE JSON line.  `value` = algorithmic attention flops of a step / step time.
+
+Beside the contract's fields the line carries stand-alone measurements taken after the timed region (HIP
+events around graph-replayed groups of launches): `per_chunk`, `append`, `kv_transfer` (request-level KV
+export / import of the batch, Sec. 3.3.4) and `decode` (one decode iteration of 64 requests x 2048 cached
+tokens on the same head shape).  Other modes: --policy / --sched-batch (prefill scheduler, Sec. 3.3.2),
+--chunk-size / --prompt-len and --layer-sweep (the saturation experiment of Sec. 2.2), --export (KV export
+inside the step at request or chunk granularity).
 """
 import argparse
 import dataclasses

@@ -65,7 +65,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
     const int part = x % p.parts;
     x /= p.parts;
     const int kh = x % p.Hkv, b = x / p.Hkv;
-    const int L = ((const const_i32 *)(uintptr_t)p.ctx)[b];
+    // a context length outside what the block table can describe is clamped: whatever the device
+    // arrays hold, no address is formed from a block-table index out of range
+    const int L = min(max(((const const_i32 *)(uintptr_t)p.ctx)[b], 0), p.max_blocks * kPage);
     const int steps = (L + 32) / 32;                     // 32-key steps over keys 0..L (key L is the new token)
     const int spp = (steps + p.parts - 1) / p.parts;     // steps per part
     const int s_begin = part * spp, s_end = min(steps, s_begin + spp);
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
     // Fused append: the workgroup whose part ends with key L caches the new token's K and V row of
     // this kv head in slot L % 16 of page block_table[b][L / 16] (16 bytes per lane; nothing in this
     // launch reads that slot: every wavefront takes key L from k_new / v_new).
-    if (p.pages_w != nullptr && s_end == steps && wave == kWaves - 1 && lane < 2 * (ROW / 16)) {
+    if (p.pages_w != nullptr && s_end == steps && wave == kWaves - 1 && lane < 2 * (ROW / 16) && L < p.max_blocks * kPage) {
         const int which = lane / (ROW / 16), chunk = lane % (ROW / 16);
         const size_t at = (size_t)bt[L / kPage] * page_bytes + ((size_t)which * p.Hkv + kh) * head_bytes
                           + (size_t)(L % kPage) * ROW + chunk * 16;
@@ -259,10 +261,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p)
     __shared__ float red[2][4];
     __shared__ float sums[G][D];
     const int b = blockIdx.x / p.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int L = p.ctx[b];
+    const int L = min(max(p.ctx[b], 0), p.max_blocks * kPage);     // clamped as in the main kernel
     const int steps = (L + 32) / 32;
     const int spp = (steps + p.parts - 1) / p.parts;
-    const int used = (steps + spp - 1) / spp;            // parts that had keys
+    const int used = (steps + spp - 1) / spp;            // parts that had keys (1 <= used <= parts)
     const float *src = p.partial + (size_t)blockIdx.x * p.parts * (D + 2);
     float ms = -INFINITY;
     for (int q = tid; q < used; q += 256) ms = fmaxf(ms, src[q * (D + 2) + D]);

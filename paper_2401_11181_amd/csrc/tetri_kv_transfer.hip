@@ -63,13 +63,14 @@ __global__ __launch_bounds__(kThreads) void kv_transfer_kernel(TransferParams p)
     j0 = __builtin_amdgcn_readfirstlane(j0);
     const int c0 = p.cu[r];
     const int n = p.cu[r + 1] - c0;
-    const int first = p.first ? p.first[r] : 0;
+    const int first = p.first ? max(p.first[r], 0) : 0;
     const int j = j0 + tid / LPR;
     if (j >= n) return;                        // no barrier below: lanes past the request's end just leave
     const int col = (tid % LPR) * 8;
     const int slabs = 2 * p.Hkv;
     const int pos = first + j;
-    const int page = p.bt[(size_t)r * p.max_blocks + pos / kPage];
+    // the block-table index is clamped: a range the table cannot describe never forms an address outside it
+    const int page = p.bt[(size_t)r * p.max_blocks + min(pos / kPage, p.max_blocks - 1)];
     // slab = kv * Hkv + head in both layouts: from one slab to the next both sides advance by a fixed step
     const int slab0 = blockIdx.y * p.slabs_per_wg;
     int left = min(slabs, slab0 + p.slabs_per_wg) - slab0;

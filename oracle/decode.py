@@ -37,3 +37,27 @@ def decode_attn(q, k_new, v_new, kv_pages, block_table, ctx_lens, scale):
             w /= w.sum()
             out[b, h] = w @ vals[:, h // g, :]
     return out
+
+
+def decode_attn_fp8(q, k_new, v_new, kv_codes, block_table, ctx_lens, scale, k_scale, v_scale):
+    """The same iteration over a cache of E4M3 codes (oracle/fp8.py): a cached K element is
+    value(code) * k_scale, a cached V element value(code) * v_scale; the new token's K and V are taken as
+    given (16-bit values, not quantised).  kv_codes [num_pages,2,Hkv,P,D] uint8."""
+    from . import fp8
+    pool = np.empty(kv_codes.shape, dtype=np.float64)
+    pool[:, 0] = fp8.dequantize(kv_codes[:, 0], k_scale)
+    pool[:, 1] = fp8.dequantize(kv_codes[:, 1], v_scale)
+    # slots that no request uses may hold the NaN code; they are never read below
+    return decode_attn(q, k_new, v_new, np.nan_to_num(pool, nan=0.0), block_table, ctx_lens, scale)
+
+
+def decode_append_fp8(k_new, v_new, kv_codes, block_table, ctx_lens, k_scale, v_scale):
+    """Caching the new tokens of a decode iteration in the E4M3 cache (in place): the codes of k_new[b] /
+    v_new[b] go to slot ctx_b % P of page block_table[b][ctx_b / P]."""
+    from . import fp8
+    P = kv_codes.shape[3]
+    for b in range(len(ctx_lens)):
+        L = int(ctx_lens[b])
+        page = int(block_table[b][L // P])
+        kv_codes[page, 0, :, L % P, :] = fp8.quantize(np.asarray(k_new[b], dtype=np.float32), k_scale)
+        kv_codes[page, 1, :, L % P, :] = fp8.quantize(np.asarray(v_new[b], dtype=np.float32), v_scale)

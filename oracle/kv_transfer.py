@@ -56,3 +56,19 @@ def kv_import(buf, kv_pages, block_table, cu_tokens, first_tokens=None):
             pos = int(first[r]) + t
             page = int(block_table[r][pos // P])
             kv_pages[page, :, :, pos % P, :] = block[:, :, t, :]
+
+
+def kv_export_fp8(kv_pages, block_table, cu_tokens, first_tokens, k_scale, v_scale):
+    """Export with quantisation (oracle/fp8.py): the same dense blocks, one E4M3 code (uint8) per element;
+    the K half of every request's block under k_scale, the V half under v_scale."""
+    from . import fp8
+    cu, _first, R = _ranges(cu_tokens, first_tokens)
+    _, _two, Hkv, _P, D = kv_pages.shape
+    dense = kv_export(np.asarray(kv_pages, dtype=np.float32), block_table, cu_tokens, first_tokens)
+    codes = np.zeros(dense.shape, dtype=np.uint8)
+    for r in range(R):
+        lo, hi = 2 * Hkv * D * int(cu[r]), 2 * Hkv * D * int(cu[r + 1])
+        half = (hi - lo) // 2
+        codes[lo:lo + half] = fp8.quantize(dense[lo:lo + half], k_scale)
+        codes[lo + half:hi] = fp8.quantize(dense[lo + half:hi], v_scale)
+    return codes

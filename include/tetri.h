@@ -288,6 +288,37 @@ TETRI_API tetri_status tetri_decode_attn_append(tetri_ctx *ctx, const void *q, c
                                                 void *stream);
 
 /*
+ * FP8 KV cache on the decode side (an extension of this build, not of the paper: the paper keeps the cache
+ * in the model's 16-bit type; Sec. 3.3.4 names the link between the instances as the scarce resource and
+ * Sec. 3.4 the decode instance's memory, and an 8-bit cache halves the bytes of both).
+ * Format: one OCP FP8 E4M3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities,
+ * largest finite value 448) per element, pool layout as kv_pages with one byte per element, and one
+ * positive finite scale per tensor: a value x is stored as the code of fl32(x * fl32(1 / scale)) clamped
+ * to [-448, 448] and rounded to nearest, ties to even; a code stands for value(code) * scale.
+ *
+ * tetri_kv_export_fp8: as tetri_kv_export from the 16-bit pool, but the dense buffer holds codes
+ *   ([2][num_kv_heads][n_r][head_dim] bytes per request, request r at byte 2 * num_kv_heads * head_dim *
+ *   cu_tokens[r]); the K half of every block under k_scale, the V half under v_scale.
+ * tetri_kv_import_fp8: scatters such a buffer of codes into an FP8 pool (bytes, bit for bit).
+ * tetri_decode_attn_fp8: tetri_decode_attn over an FP8 pool: cached K and V are value(code) * k_scale and
+ *   value(code) * v_scale, the new token's k_new / v_new (bf16) enter unquantised; with append = 1 the
+ *   codes of k_new[b] / v_new[b] are also written to slot ctx_lens[b] of the pool (then kv_pages_fp8 is
+ *   in/out and block_table must cover that position), with append = 0 the pool is only read.
+ * Other arguments, errors and the scratch-memory rule as for the 16-bit calls; TETRI_ERR_INVALID_ARG for
+ * scales that are not positive and finite.
+ */
+TETRI_API tetri_status tetri_kv_export_fp8(tetri_ctx *ctx, const void *kv_pages, const int32_t *block_table,
+                                           const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
+                                           int64_t total_tokens, float k_scale, float v_scale, void *buf, void *stream);
+TETRI_API tetri_status tetri_kv_import_fp8(tetri_ctx *ctx, const void *buf, const int32_t *block_table,
+                                           const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
+                                           int64_t total_tokens, void *kv_pages_fp8, void *stream);
+TETRI_API tetri_status tetri_decode_attn_fp8(tetri_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                                             void *kv_pages_fp8, const int32_t *block_table, const int32_t *ctx_lens,
+                                             int32_t num_reqs, int32_t max_ctx_len, float scale, float k_scale,
+                                             float v_scale, int32_t append, void *out, void *stream);
+
+/*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
  * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
  * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages

@@ -60,7 +60,8 @@ def encode(y):
 def quantize(x, scale):
     """Codes of cache values x (float32 holding bf16 values) under one per-tensor scale."""
     inv = np.float32(1.0) / np.float32(scale)
-    return encode(np.asarray(x, dtype=np.float32) * inv)
+    with np.errstate(over="ignore"):                   # a product that overflows to infinity saturates below
+        return encode(np.asarray(x, dtype=np.float32) * inv)
 
 
 def dequantize(codes, scale):

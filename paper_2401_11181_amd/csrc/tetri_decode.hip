@@ -21,6 +21,14 @@
 //     (O, m, l) and a second small kernel merges them in a fixed order: results are deterministic.
 // Keys past the end of a request's cache are loaded from a row of zeros and masked, so that stale
 // page contents (which may be NaN bit patterns) never reach an MFMA.
+//
+// FP8 cache (template flag FP8; this build's extension, not the paper's): the pool holds E4M3 codes with
+// one scale per tensor.  The codes of a step travel through registers (16 per lane and load, requested
+// one step ahead), are converted to bf16 pairs by v_cvt_scalef32_pk_bf16_fp8 (exact: a code has four
+// significant bits) and written into the same swizzled LDS tiles; everything after that is shared with
+// the 16-bit path.  The scales are not applied per element: the K scale multiplies the scores of cached
+// keys, the V scale the finished output; the new token, which is not quantised, gets the inverse factors
+// on its score and on its weight in the last step.
 #include "attn_common.h"
 
 namespace {
@@ -49,11 +57,14 @@ __device__ __forceinline__ void issue_tile(const char *page_lo, const char *page
 }
 
 // grid: num_reqs * Hkv * parts workgroups, part fastest
-template <int D>
+template <int D, bool FP8>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParams p)
 {
     constexpr int KSTEPS = D / 16, DBLK = D / 32, NI = D / 16;
-    constexpr int ROW = D * 2, TILE_BYTES = 32 * ROW;
+    constexpr int ROW = D * 2, TILE_BYTES = 32 * ROW;      // rows and tiles in LDS are bf16 in both paths
+    constexpr int ESZ = FP8 ? 1 : 2;                       // bytes of a cache element
+    // FP8: a lane loads 16 codes; LPR lanes cover a row, a load instruction RPI rows, NL loads a tile
+    constexpr int LPR = D / 16, RPI = 64 / LPR, NL = 32 / RPI;
     static_assert(NI == 4 || NI == 8, "wait counts below");
     __shared__ __attribute__((aligned(1024))) char smem[kWaves * 2 * TILE_BYTES];
     __shared__ float stat[kWaves][2][32];
@@ -74,7 +85,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
     if (s_begin >= s_end) return;                        // fewer steps than parts: the merge kernel skips this part too
 
     const const_i32 *bt = (const const_i32 *)(uintptr_t)(p.bt + (size_t)b * p.max_blocks);
-    const size_t head_bytes = (size_t)kPage * ROW, page_bytes = 2 * (size_t)p.Hkv * head_bytes;
+    const size_t head_bytes = (size_t)kPage * D * ESZ, page_bytes = 2 * (size_t)p.Hkv * head_bytes;
     const char *pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * head_bytes;
     const char *pool_v = pool_k + (size_t)p.Hkv * head_bytes;
     const char *new_k = reinterpret_cast<const char *>(p.k_new) + ((size_t)b * p.Hkv + kh) * ROW;
@@ -93,21 +104,80 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
         issue_tile<D>(pool_v + page_of(step, 0), pool_v + page_of(step, 1), new_v, step * 32, L, true, lane, v_lds);
     };
 
+    // FP8: the codes of one matrix of one step, 16 per lane and load; keys at and past L load nothing
+    [[maybe_unused]] u32x4 rk[NL], rv[NL];
+    auto load_codes = [&](const char *pool, int step, u32x4 (&raw)[NL]) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int r = i * RPI + lane / LPR;
+            const char *src = pool + page_of(step, (i * RPI) / kPage) + (size_t)(r % kPage) * D + (lane % LPR) * 16;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (step * 32 + r < L) v = *reinterpret_cast<const u32x4 *>(src);
+            raw[i] = v;
+        }
+    };
+    // ... converted to bf16 and written to the wavefront's tile: codes c16*16 .. +15 of row r are two
+    // 16-byte chunks of the bf16 row
+    auto write_codes = [&](const u32x4 (&raw)[NL], bool is_v) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int r = i * RPI + lane / LPR, c16 = lane % LPR;
+            u32x4 lo, hi;
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                lo[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][w], 1.0f, false));
+                lo[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][w], 1.0f, true));
+                hi[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][2 + w], 1.0f, false));
+                hi[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][2 + w], 1.0f, true));
+            }
+            const int swz = is_v ? v_swizzle<D>(r) : k_swizzle<D>(r);
+            char *row = my + (is_v ? TILE_BYTES : 0) + r * ROW;
+            *reinterpret_cast<u32x4 *>(row + (((2 * c16) ^ swz) << 4)) = lo;
+            *reinterpret_cast<u32x4 *>(row + (((2 * c16 + 1) ^ swz) << 4)) = hi;
+        }
+    };
+
     // the first step's K and V are requested before anything else is read
     int st = s_begin + wave;
     if (st < s_end) {
-        issue_k(st);
-        issue_v(st);
+        if constexpr (FP8) {
+            load_codes(pool_k, st, rk);
+            load_codes(pool_v, st, rv);
+        } else {
+            issue_k(st);
+            issue_v(st);
+        }
     }
     // Fused append: the workgroup whose part ends with key L caches the new token's K and V row of
     // this kv head in slot L % 16 of page block_table[b][L / 16] (16 bytes per lane; nothing in this
     // launch reads that slot: every wavefront takes key L from k_new / v_new).
+    // With an FP8 cache the row is quantised on the way: fl32(x * inv_scale) clamped to +-448, rounded to
+    // nearest even by v_cvt_pk_fp8_f32, 8 codes per lane.
     if (p.pages_w != nullptr && s_end == steps && wave == kWaves - 1 && lane < 2 * (ROW / 16) && L < p.max_blocks * kPage) {
         const int which = lane / (ROW / 16), chunk = lane % (ROW / 16);
         const size_t at = (size_t)bt[L / kPage] * page_bytes + ((size_t)which * p.Hkv + kh) * head_bytes
-                          + (size_t)(L % kPage) * ROW + chunk * 16;
-        const uint4 v = *reinterpret_cast<const uint4 *>((which ? new_v : new_k) + chunk * 16);
-        *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(p.pages_w) + at) = v;
+                          + ((size_t)(L % kPage) * ROW + chunk * 16) / 2 * ESZ;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>((which ? new_v : new_k) + chunk * 16);
+        if constexpr (FP8) {
+            const float inv = which ? p.v_inv : p.k_inv;
+            uint32_t codes[2];
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t word = v[2 * w + e / 2];
+                    const float x = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+                    y[e] = __builtin_fminf(__builtin_fmaxf(x * inv, -448.0f), 448.0f);
+                }
+                int c = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+                c = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], c, true);
+                codes[w] = (uint32_t)c;
+            }
+            *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(p.pages_w) + at) = make_uint2(codes[0], codes[1]);
+        } else {
+            *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(p.pages_w) + at) = v;
+        }
     }
     // Q fragments (B operand of S^T = K Q^T): column l32 is query head kh * g + l32, zero past g
     bf16x8 qf[KSTEPS];
@@ -140,20 +210,43 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
     float m = -1e30f, lsum = 0.f;
-    const float c = p.neg ? -p.c : p.c;
+    // FP8: the tiles hold code values; the K scale rides on the score factor (sign of c unchanged: scales
+    // are positive)
+    const float c = (p.neg ? -p.c : p.c) * (FP8 ? p.k_scale : 1.0f);
     const float masked = p.neg ? INFINITY : -INFINITY;
     bf16x2 ones;
     ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 
     for (; st < s_end; st += kWaves) {
         const bool more = st + kWaves < s_end;
-        // K of this step has landed when only the V loads behind it are outstanding
-        wait_vm<NI>();
+        if constexpr (FP8) {
+            // this step's codes (the compiler waits for the loads) become bf16 tiles; the row of the new
+            // token, not quantised, is copied over its zeros; then the next step's codes are requested
+            write_codes(rk, false);
+            write_codes(rv, true);
+            if (st == steps - 1 && lane < ROW / 16) {
+                const int r = L - st * 32;
+                *reinterpret_cast<u32x4 *>(my + r * ROW + ((lane ^ k_swizzle<D>(r)) << 4)) =
+                    *reinterpret_cast<const u32x4 *>(new_k + lane * 16);
+                *reinterpret_cast<u32x4 *>(my + TILE_BYTES + r * ROW + ((lane ^ v_swizzle<D>(r)) << 4)) =
+                    *reinterpret_cast<const u32x4 *>(new_v + lane * 16);
+            }
+            if (more) {
+                load_codes(pool_k, st + kWaves, rk);
+                load_codes(pool_v, st + kWaves, rv);
+            }
+            asm volatile("" ::: "memory");               // the fragment reads below stay behind the tile writes
+        } else {
+            // K of this step has landed when only the V loads behind it are outstanding
+            wait_vm<NI>();
+        }
         bf16x8 kf[KSTEPS];
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(my + kbase[s]));
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // fragments are in registers: the tile may be overwritten
-        if (more) issue_k(st + kWaves);
+        if constexpr (!FP8) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // fragments are in registers: the tile may be overwritten
+            if (more) issue_k(st + kWaves);
+        }
         f32x16 sc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) sc[v] = 0.f;
@@ -164,6 +257,13 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 if (st * 32 + (v / 4) * 8 + 4 * half + (v % 4) > L) sc[v] = masked;
+        }
+        if constexpr (FP8) {
+            if (st == steps - 1) {                       // the new token's key carries no K scale
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (st * 32 + (v / 4) * 8 + 4 * half + (v % 4) == L) sc[v] *= p.k_inv;
+            }
         }
         float mx = sc[0] * c;
 #pragma unroll
@@ -184,13 +284,25 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
             pf[v / 8][v % 8 + 1] = pp[1];
         }
         lsum = lsum * alpha + l_blk;
+        if constexpr (FP8) {
+            // ... and its value no V scale: the finished output is multiplied by the V scale, so the new
+            // token's weight is divided by it
+            if (st == steps - 1) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (st * 32 + (v / 4) * 8 + 4 * half + (v % 4) == L)
+                        pf[v / 8][v % 8] = (__bf16)((float)pf[v / 8][v % 8] * p.v_inv);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < DBLK; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
-        // V of this step: behind it only the next step's K loads
-        if (more) wait_vm<NI>();
-        else wait_vm<0>();
+        if constexpr (!FP8) {
+            // V of this step: behind it only the next step's K loads
+            if (more) wait_vm<NI>();
+            else wait_vm<0>();
+        }
         s16x8 vf[2 * DBLK];
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -201,8 +313,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
                 const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * ROW));
                 vf[j * DBLK + db] = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (more) issue_v(st + kWaves);
+        if constexpr (!FP8) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (more) issue_v(st + kWaves);
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -241,7 +355,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
         }
         const size_t head = (size_t)b * p.Hq + (size_t)kh * p.g + col;
         if (p.parts == 1) {
-            p.out[head * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+            p.out[head * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l * p.out_scale));
         } else {
             float *dst = p.partial + (head * p.parts + part) * (D + 2);
             dst[d] = acc;
@@ -293,7 +407,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p)
     if (grp == 0) {
 #pragma unroll
         for (int g = 1; g < G; ++g) acc += sums[g][d];
-        p.out[(size_t)blockIdx.x * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l));
+        p.out[(size_t)blockIdx.x * D + d] = __builtin_bit_cast(uint16_t, (__bf16)(acc / l * p.out_scale));
     }
 }
 
@@ -303,8 +417,10 @@ hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStr
 {
     const dim3 grid(p.B * p.Hkv * p.parts), block(kWaves * 64);
     const int d = h->cfg.head_dim;
-    if (d == 128) hipLaunchKernelGGL(decode_attn_kernel<128>, grid, block, 0, stream, p);
-    else if (d == 64) hipLaunchKernelGGL(decode_attn_kernel<64>, grid, block, 0, stream, p);
+    if (d == 128 && !p.fp8) hipLaunchKernelGGL((decode_attn_kernel<128, false>), grid, block, 0, stream, p);
+    else if (d == 64 && !p.fp8) hipLaunchKernelGGL((decode_attn_kernel<64, false>), grid, block, 0, stream, p);
+    else if (d == 128) hipLaunchKernelGGL((decode_attn_kernel<128, true>), grid, block, 0, stream, p);
+    else if (d == 64) hipLaunchKernelGGL((decode_attn_kernel<64, true>), grid, block, 0, stream, p);
     else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.parts == 1) return e;

@@ -319,9 +319,12 @@ tetri_status tetri_kv_append(tetri_ctx *h, const void *k_new, const void *v_new,
     return TETRI_OK;
 }
 
+// mode 0: 16-bit pool <-> 16-bit buffer; 1: 16-bit pool -> buffer of FP8 codes (quantising);
+// 2: FP8 pool <-> buffer of FP8 codes (bytes)
 static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, void *buf, const int32_t *block_table,
                                 const int32_t *cu_tokens, const int32_t *first_tokens, int32_t num_reqs,
-                                int64_t total_tokens, bool to_pool, void *stream)
+                                int64_t total_tokens, bool to_pool, void *stream, int mode = 0, float k_scale = 1.f,
+                                float v_scale = 1.f)
 {
     if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
     if (!kv_pages || !aligned16(kv_pages)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: kv_pages is null or not 16-byte aligned", fn);
@@ -333,7 +336,11 @@ static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, vo
                     (long long)total_tokens, (long long)most);
     if (total_tokens == 0) return TETRI_OK;
     if (!buf || !aligned16(buf)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: buf is null or not 16-byte aligned", fn);
-    const int64_t tile_tokens = 2048 / h->cfg.head_dim;     // a workgroup's tile: 4 KB per (K / V, head) slab
+    if (mode == 1 && !(std::isfinite(k_scale) && std::isfinite(v_scale) && k_scale > 0.f && v_scale > 0.f))
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: k_scale and v_scale must be positive and finite", fn);
+    // 16-bit units of a row as the kernel moves it: an FP8 row of head_dim codes is head_dim / 2 units
+    const int32_t row_units = mode == 2 ? h->cfg.head_dim / 2 : h->cfg.head_dim;
+    const int64_t tile_tokens = 2048 / row_units;           // a workgroup's tile: 256 lanes of 16 bytes per slab
     const int64_t tiles = total_tokens / tile_tokens + num_reqs;     // >= sum of ceil(n_r / tile_tokens)
     if (tiles > 0x7fffffff) return fail(h, TETRI_ERR_INVALID_ARG, "%s: too many tokens for one launch", fn);
     int dev = -1;
@@ -351,9 +358,27 @@ static tetri_status kv_transfer(const char *fn, tetri_ctx *h, void *kv_pages, vo
     const int64_t want = 8 * (int64_t)std::max(h->num_cus, 1);
     p.slabs_per_wg = (int32_t)std::min<int64_t>(slabs, std::max<int64_t>(1, tiles * slabs / want));
     if (h->transfer_slabs > 0) p.slabs_per_wg = (int32_t)std::min<int64_t>(slabs, h->transfer_slabs);
-    hipError_t e = tetri_launch_kv_transfer(h, p, (int32_t)tiles, to_pool, static_cast<hipStream_t>(stream));
+    p.k_inv = 1.0f / k_scale; p.v_inv = 1.0f / v_scale;
+    hipError_t e = mode == 1 ? tetri_launch_kv_export_fp8(h, p, (int32_t)tiles, static_cast<hipStream_t>(stream))
+                             : tetri_launch_kv_transfer(h, p, row_units, (int32_t)tiles, to_pool, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;
+}
+
+tetri_status tetri_kv_export_fp8(tetri_ctx *h, const void *kv_pages, const int32_t *block_table, const int32_t *cu_tokens,
+                                 const int32_t *first_tokens, int32_t num_reqs, int64_t total_tokens, float k_scale,
+                                 float v_scale, void *buf, void *stream)
+{
+    return kv_transfer("tetri_kv_export_fp8", h, const_cast<void *>(kv_pages), buf, block_table, cu_tokens, first_tokens,
+                       num_reqs, total_tokens, false, stream, 1, k_scale, v_scale);
+}
+
+tetri_status tetri_kv_import_fp8(tetri_ctx *h, const void *buf, const int32_t *block_table, const int32_t *cu_tokens,
+                                 const int32_t *first_tokens, int32_t num_reqs, int64_t total_tokens, void *kv_pages_fp8,
+                                 void *stream)
+{
+    return kv_transfer("tetri_kv_import_fp8", h, kv_pages_fp8, const_cast<void *>(buf), block_table, cu_tokens,
+                       first_tokens, num_reqs, total_tokens, true, stream, 2);
 }
 
 tetri_status tetri_kv_export(tetri_ctx *h, const void *kv_pages, const int32_t *block_table, const int32_t *cu_tokens,
@@ -373,7 +398,7 @@ tetri_status tetri_kv_import(tetri_ctx *h, const void *buf, const int32_t *block
 static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
                                   const void *kv_pages, void *kv_pages_w, const int32_t *block_table,
                                   const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len, float scale, void *out,
-                                  void *stream)
+                                  void *stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f)
 {
     if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
     const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
@@ -409,6 +434,12 @@ static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, c
     p.max_blocks = cfg.max_blocks_per_seq;
     p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     p.neg = scale < 0.f;
+    if (fp8 && !(std::isfinite(k_scale) && std::isfinite(v_scale) && k_scale > 0.f && v_scale > 0.f))
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: k_scale and v_scale must be positive and finite", fn);
+    p.fp8 = fp8;
+    p.k_scale = k_scale; p.v_scale = v_scale;
+    p.k_inv = 1.0f / k_scale; p.v_inv = 1.0f / v_scale;
+    p.out_scale = fp8 ? v_scale : 1.0f;
     // Few requests: split every request's keys over several workgroups until the device has four
     // workgroups per compute unit, each with at least eight 32-key steps, as far as the scratch
     // memory for the parts reaches.
@@ -433,6 +464,16 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
 {
     return decode_common("tetri_decode_attn", h, q, k_new, v_new, kv_pages, nullptr, block_table, ctx_lens, num_reqs,
                          max_ctx_len, scale, out, stream);
+}
+
+tetri_status tetri_decode_attn_fp8(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, void *kv_pages_fp8,
+                                   const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs,
+                                   int32_t max_ctx_len, float scale, float k_scale, float v_scale, int32_t append,
+                                   void *out, void *stream)
+{
+    if (append != 0 && append != 1) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_decode_attn_fp8: append must be 0 or 1");
+    return decode_common("tetri_decode_attn_fp8", h, q, k_new, v_new, kv_pages_fp8, append ? kv_pages_fp8 : nullptr,
+                         block_table, ctx_lens, num_reqs, max_ctx_len, scale, out, stream, true, k_scale, v_scale);
 }
 
 tetri_status tetri_decode_attn_append(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, void *kv_pages,

@@ -66,6 +66,7 @@ struct TransferParams {
     const int32_t *bt, *cu, *first;   // first may be null: every range starts at token 0
     int32_t R, Hkv, max_blocks;
     int32_t slabs_per_wg; // (K / V, head) slabs one workgroup moves
+    float k_inv, v_inv;   // quantising export: fl32(1 / scale) of the K and of the V half
 };
 
 // Launch parameters of the decode-iteration kernels.
@@ -79,11 +80,15 @@ struct DecodeParams {
     int32_t parts;        // workgroups that share one (request, kv head)'s keys
     float c;              // |scale| * log2(e)
     int32_t neg;          // 1 if scale < 0
+    int32_t fp8;          // 1: the pool holds E4M3 codes (one byte per element) with per-tensor scales
+    float k_scale, v_scale, k_inv, v_inv;   // the scales and fl32(1 / scale)
+    float out_scale;      // factor on the finished output: v_scale for an FP8 pool, else 1
 };
 
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
 hipError_t tetri_launch_attn_split(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
-hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t tiles, bool to_pool,
-                                    hipStream_t stream);
+hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t row_units, int32_t tiles,
+                                    bool to_pool, hipStream_t stream);
+hipError_t tetri_launch_kv_export_fp8(const tetri_ctx *h, const TransferParams &p, int32_t tiles, hipStream_t stream);
 hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStream_t stream);
 hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

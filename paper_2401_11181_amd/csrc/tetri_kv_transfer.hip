@@ -102,14 +102,82 @@ __global__ __launch_bounds__(kThreads) void kv_transfer_kernel(TransferParams p)
     if (left) st(ld());
 }
 
+// Export with quantisation: the 16-bit pool is gathered into a dense buffer of FP8 E4M3 codes, the K
+// half of every request's block under the K scale, the V half under the V scale (this build's extension:
+// half the bytes on the link between the instances).  A code is fl32(x * inv_scale) clamped to +-448 and
+// rounded to nearest even by v_cvt_pk_fp8_f32.  Same work split as the copy kernel: a lane reads 16 bytes
+// (8 values) and writes 8 codes.
+template <int D>
+__global__ __launch_bounds__(kThreads) void kv_export_fp8_kernel(TransferParams p)
+{
+    constexpr int LPR = D / 8, TILE = kThreads / LPR;
+    const int tid = threadIdx.x;
+    int j0 = 0;
+    const int r = __builtin_amdgcn_readfirstlane(find_request<TILE>(p.cu, p.R, blockIdx.x, tid & 63, j0));
+    if (r < 0) return;
+    j0 = __builtin_amdgcn_readfirstlane(j0);
+    const int c0 = p.cu[r];
+    const int n = p.cu[r + 1] - c0;
+    const int first = p.first ? max(p.first[r], 0) : 0;
+    const int j = j0 + tid / LPR;
+    if (j >= n) return;
+    const int col = (tid % LPR) * 8;
+    const int slabs = 2 * p.Hkv;
+    const int pos = first + j;
+    const int page = p.bt[(size_t)r * p.max_blocks + min(pos / kPage, p.max_blocks - 1)];
+    const int slab0 = blockIdx.y * p.slabs_per_wg;
+    const int slab_end = min(slabs, slab0 + p.slabs_per_wg);
+    const size_t pool_step = (size_t)kPage * D, buf_step = (size_t)n * D;
+    const uint16_t *src = p.pool + ((size_t)page * slabs + slab0) * pool_step + (size_t)(pos % kPage) * D + col;
+    uint8_t *dst = reinterpret_cast<uint8_t *>(p.buf) + (size_t)slabs * D * c0 + slab0 * buf_step + (size_t)j * D + col;
+#pragma unroll 2
+    for (int slab = slab0; slab < slab_end; ++slab) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        const float inv = slab < p.Hkv ? p.k_inv : p.v_inv;
+        uint32_t codes[2];
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t word = v[2 * w + e / 2];
+                const float x = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+                y[e] = __builtin_fminf(__builtin_fmaxf(x * inv, -448.0f), 448.0f);
+            }
+            int c = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+            c = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], c, true);
+            codes[w] = (uint32_t)c;
+        }
+        __builtin_nontemporal_store(codes[0], reinterpret_cast<uint32_t *>(dst));
+        __builtin_nontemporal_store(codes[1], reinterpret_cast<uint32_t *>(dst) + 1);
+        src += pool_step;
+        dst += buf_step;
+    }
+}
+
 }  // namespace
 
-hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t tiles, bool to_pool,
-                                    hipStream_t stream)
+hipError_t tetri_launch_kv_export_fp8(const tetri_ctx *h, const TransferParams &p, int32_t tiles, hipStream_t stream)
 {
     dim3 grid(tiles, (2 * p.Hkv + p.slabs_per_wg - 1) / p.slabs_per_wg), block(kThreads);
     const int d = h->cfg.head_dim;
-    if (d == 128) {
+    if (d == 128) hipLaunchKernelGGL(kv_export_fp8_kernel<128>, grid, block, 0, stream, p);
+    else if (d == 64) hipLaunchKernelGGL(kv_export_fp8_kernel<64>, grid, block, 0, stream, p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// `row_units`: 16-bit units of one row of the pool (head_dim for a 16-bit pool, head_dim / 2 for FP8 codes,
+// which the copy moves as opaque bytes)
+hipError_t tetri_launch_kv_transfer(const tetri_ctx *, const TransferParams &p, int32_t row_units, int32_t tiles,
+                                    bool to_pool, hipStream_t stream)
+{
+    dim3 grid(tiles, (2 * p.Hkv + p.slabs_per_wg - 1) / p.slabs_per_wg), block(kThreads);
+    const int d = row_units;
+    if (d == 32) {
+        if (to_pool) hipLaunchKernelGGL((kv_transfer_kernel<32, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((kv_transfer_kernel<32, false>), grid, block, 0, stream, p);
+    } else if (d == 128) {
         if (to_pool) hipLaunchKernelGGL((kv_transfer_kernel<128, true>), grid, block, 0, stream, p);
         else hipLaunchKernelGGL((kv_transfer_kernel<128, false>), grid, block, 0, stream, p);
     } else if (d == 64) {

@@ -77,6 +77,12 @@ def lib():
         L.tetri_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.tetri_decode_attn_append.restype = i32
         L.tetri_decode_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
+        L.tetri_kv_export_fp8.restype = i32
+        L.tetri_kv_export_fp8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, f32, f32, vp, vp]
+        L.tetri_kv_import_fp8.restype = i32
+        L.tetri_kv_import_fp8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
+        L.tetri_decode_attn_fp8.restype = i32
+        L.tetri_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, i32, vp, vp]
         L.tetri_kv_export.restype = i32
         L.tetri_kv_export.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
         L.tetri_kv_import.restype = i32
@@ -247,6 +253,25 @@ class Tetri:
         self._check(lib().tetri_decode_attn_append(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
                                                    _ptr(block_table), _ptr(ctx_lens), int(num_reqs), int(max_ctx_len),
                                                    float(scale), _ptr(out), _stream(stream)))
+
+    def tetri_kv_export_fp8(self, kv_pages, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, k_scale,
+                            v_scale, buf, stream=None):
+        self._check(lib().tetri_kv_export_fp8(self.h, _ptr(kv_pages), _ptr(block_table), _ptr(cu_tokens),
+                                              _ptr(first_tokens), int(num_reqs), int(total_tokens), float(k_scale),
+                                              float(v_scale), _ptr(buf), _stream(stream)))
+
+    def tetri_kv_import_fp8(self, buf, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, kv_pages_fp8,
+                            stream=None):
+        self._check(lib().tetri_kv_import_fp8(self.h, _ptr(buf), _ptr(block_table), _ptr(cu_tokens),
+                                              _ptr(first_tokens), int(num_reqs), int(total_tokens), _ptr(kv_pages_fp8),
+                                              _stream(stream)))
+
+    def tetri_decode_attn_fp8(self, q, k_new, v_new, kv_pages_fp8, block_table, ctx_lens, num_reqs, max_ctx_len, scale,
+                              k_scale, v_scale, append, out, stream=None):
+        self._check(lib().tetri_decode_attn_fp8(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages_fp8),
+                                                _ptr(block_table), _ptr(ctx_lens), int(num_reqs), int(max_ctx_len),
+                                                float(scale), float(k_scale), float(v_scale), int(append), _ptr(out),
+                                                _stream(stream)))
 
     def tetri_kv_export(self, kv_pages, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, buf,
                         stream=None):

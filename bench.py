@@ -323,8 +323,18 @@ def main():
             "frac": round(kv_bytes / (dec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "tokens_per_s": round(dB / (dec_ms * 1e-3), 1),
         }
+        # the same iteration over an FP8 E4M3 cache (this build's extension): half the bytes
+        dcodes = torch.randint(0, 0x78, tuple(dpool.shape), dtype=torch.uint8, device=dev, generator=gen)
+        dec8_ms = group_time(lambda: dh.tetri_decode_attn_fp8(dq, dk, dv, dcodes, dbt, dcl, dB, dctx, w.scale,
+                                                              1.0 / 64, 1.0 / 64, 0, dout))
+        result["decode"]["fp8"] = {
+            "kernel": "decode_attn_kernel<D, FP8> (same batch, cache of E4M3 codes)", "kv_bytes": kv_bytes // 2,
+            "ms": round(dec8_ms, 5), "achieved_GBs": round(kv_bytes / 2 / (dec8_ms * 1e-3) / 1e9, 1),
+            "frac": round(kv_bytes / 2 / (dec8_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "tokens_per_s": round(dB / (dec8_ms * 1e-3), 1),
+        }
         dh.close()
-        del dpool
+        del dpool, dcodes
 
     # ---- the CPU oracle on the host cores of this machine (reported baseline, not the target)
     if not args.no_cpu_baseline:

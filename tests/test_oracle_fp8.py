@@ -125,3 +125,13 @@ def test_decode_append_fp8_places_the_codes():
     assert t[codes[2, 0, 0, 1]].tolist() == [1.0, -2.0] and t[codes[2, 1, 0, 1]].tolist() == [1.5, 0.125]
     assert t[codes[0, 0, 0, 0]].tolist() == [0.5, 448.0] and t[codes[0, 1, 0, 0]].tolist() == [-0.5, 4.0]
     assert (codes == 0x7F).sum() == codes.size - 8
+
+
+def test_the_product_is_rounded_to_float32_before_the_code_is_chosen():
+    """Two inputs where the definition's single-precision product and an exact division fall on different
+    sides of a code boundary.  x = 4.5 * 2^-10 with scale 0.3f: fl32(1 / 0.3f) = 3.33333325..., the product
+    0.01464843712... rounds in float32 to 7.5 * 2^-9 exactly, a tie between the codes 7 and 8 -> 8 (even);
+    the exact quotient 0.014648436918 lies below the tie and would give 7.  With scale 1.7f and
+    x = 0.02490234375 the float32 product lies below the same tie (-> 7), the exact quotient above it."""
+    assert int(fp8.quantize(np.float32(4.5 * 2.0 ** -10), 0.3)) == 0x08
+    assert int(fp8.quantize(np.float32(0.02490234375), 1.7)) == 0x07

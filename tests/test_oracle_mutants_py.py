@@ -10,11 +10,28 @@ import types
 import pytest
 
 import test_oracle_decode as decode_pins
+import test_oracle_fp8 as fp8_pins
 import test_oracle_kv_transfer as transfer_pins
-from oracle import decode, kv_transfer
+from oracle import decode, fp8, kv_transfer
 
 TRANSFER_SRC = inspect.getsource(kv_transfer)
 DECODE_SRC = inspect.getsource(decode)
+FP8_SRC = inspect.getsource(fp8)
+
+FP8_MUTANTS = {
+    "exponent-bias": ("            t[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)", "            t[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 8)"),
+    "subnormal-exponent": ("            t[code] = sign * (m / 8.0) * 2.0 ** -6", "            t[code] = sign * (m / 8.0) * 2.0 ** -7"),
+    "mantissa-bits": ("        e, m = (code >> 3) & 0xF, code & 0x7", "        e, m = (code >> 3) & 0xF, (code & 0x7) >> 1 << 1"),
+    "nan-is-a-number": ("        if e == 0xF and m == 0x7:", "        if e == 0xF and m == 0x8:"),
+    "ties-away-from-zero": ("                code = lo if lo % 2 == 0 else hi      # consecutive", "                code = hi      # consecutive"),
+    "round-down": ("            if d_lo < d_hi:", "            if d_lo <= d_hi + 1e300:"),
+    "no-saturation": ("    flat = np.clip(y.reshape(-1), -MAX, MAX)", "    flat = np.clip(y.reshape(-1), -480.0, 480.0) * (np.abs(y.reshape(-1)) <= 464.0)"),
+    "sign-lost": ("        out[i] = code | (0x80 if (v < 0 or (v == 0 and np.signbit(v))) else 0)", "        out[i] = code"),
+    "divides-in-double": ("    inv = np.float32(1.0) / np.float32(scale)\n    with np.errstate(over=\"ignore\"):                   # a product that overflows to infinity saturates below\n        return encode(np.asarray(x, dtype=np.float32) * inv)",
+                          "    return encode((np.asarray(x, dtype=np.float64) * 3.0) / (np.float64(scale) * 3.0))"),
+    "dequantize-forgets-scale": ("    return decode_table()[np.asarray(codes, dtype=np.uint8)] * np.float64(np.float32(scale))",
+                                 "    return decode_table()[np.asarray(codes, dtype=np.uint8)]"),
+}
 
 TRANSFER_MUTANTS = {
     "export-slot-for-page": ("            block[:, :, t, :] = kv_pages[page, :, :, pos % P, :]",
@@ -79,6 +96,8 @@ def test_every_mutation_site_exists():
         assert TRANSFER_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
     for name, (old, _new) in DECODE_MUTANTS.items():
         assert DECODE_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
+    for name, (old, _new) in FP8_MUTANTS.items():
+        assert FP8_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
 
 
 @pytest.mark.parametrize("name", sorted(TRANSFER_MUTANTS))
@@ -95,6 +114,36 @@ def test_decode_pins_catch_mutant(name, oracle):
     assert run_pins(decode_pins, "decode", mutant, oracle), "no pin noticed the planted mistake '%s'" % name
 
 
+def run_fp8_pins(mutant):
+    """The FP8 pins reach the codes through three modules: all of them see the mutant."""
+    import oracle as opkg
+    real = fp8_pins.fp8
+    caught = []
+    fp8_pins.fp8 = mutant
+    opkg.fp8 = mutant
+    import sys
+    sys.modules["oracle.fp8"] = mutant
+    try:
+        for f in pin_functions(fp8_pins):
+            try:
+                f()
+            except (AssertionError, ValueError, IndexError, FloatingPointError):
+                caught.append(f.__name__)
+    finally:
+        fp8_pins.fp8 = real
+        opkg.fp8 = real
+        sys.modules["oracle.fp8"] = real
+    return caught
+
+
+@pytest.mark.parametrize("name", sorted(FP8_MUTANTS))
+def test_fp8_pins_catch_mutant(name):
+    old, new = FP8_MUTANTS[name]
+    mutant = module_from(FP8_SRC.replace(old, new), "fp8_mutant_" + name.replace("-", "_"))
+    assert run_fp8_pins(mutant), "no pin noticed the planted mistake '%s'" % name
+
+
 def test_unmutated_oracles_pass_the_same_calls(oracle):
+    assert run_fp8_pins(fp8) == []
     assert run_pins(transfer_pins, "kv_transfer", kv_transfer, oracle) == []
     assert run_pins(decode_pins, "decode", decode, oracle) == []

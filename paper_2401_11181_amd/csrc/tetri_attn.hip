@@ -798,31 +798,33 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // by job.  Without key-range splitting the jobs of a group are its row tiles, late (long) ones
     // first.  With it (helpers != 0): first the tiles but the last one of the host's bound (which
     // exists only if the chunk has ragged segments), then the helpers, each doing the last third
-    // of the key ranges of two of those tiles, then that last tile and its helper: what is
-    // probably empty starts last.
+    // of the key ranges of two of those tiles.  The bound's last tile gets no workgroups of its own
+    // (they would start when the first compute unit becomes free and, though empty, end after
+    // everybody else: kernel start-up and the look-up take 2-3 us): its two pieces are one more job of
+    // the workgroup of tile 0, whose key range is the shortest, and of the last helper.
     const int xcd = abid % kXcd, local = abid / kXcd;
     const int job = magic_div(local, p.gpx_magic);
     const int grp = xcd * p.gpx + (local - job * p.gpx);
     const int T = p.tiles, H = p.helpers;
-    if (grp >= p.groups || job >= T + H) return;
+    if (grp >= p.groups || job >= (H != 0 ? T + H - 2 : T)) return;
     if (threadIdx.x == 0) params = p;                // from scalar registers: no memory read to wait for
-    int piece = 0, first = T - 1 - job, count = 1;
+    int piece = 0, first = T - 1 - job, count = 1, extra = 0;
     if (H != 0) {
         if (job < T - 1) {
             first = T - 2 - job;
-        } else if (job < T + H - 2) {
+            extra = first == 0;
+        } else {
             piece = 1;
             first = T - 2 - 2 * (job - (T - 1));
             count = min(2, first + 1);
-        } else {
-            piece = job - (T + H - 2);
-            first = T - 1;
+            extra = job == T + H - 3;
         }
     }
     Handover ho;
-    for (int i = 0; i < count; ++i) {
+    for (int i = 0; i < count + extra; ++i) {
         if (i != 0) __syncthreads();                 // the stage buffers change hands
-        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, first - i, piece, ho, i + 1 < count);
+        // only the hand-over of a helper's first tile is left open while it does its second one
+        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, i < count ? first - i : T - 1, piece, ho, i + 1 < count);
     }
     // ---- a helper's first tile whose hand-over was left open: if the other piece has arrived in the
     // meantime (it found the counter at 0 and went away), this wavefront finishes the tile from its

@@ -539,8 +539,9 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
                 return fail(h, TETRI_ERR_INVALID_ARG, "%s: the current device is %d, the handle was created on device %d", fn, dev, h->device);
         }
         p.gpx = (groups + 7) / 8;
-        p.attn_grid = 8 * p.gpx * (p.tiles + p.helpers);
-        p.attn_first = p.helpers ? 8 * p.gpx * (p.tiles + p.helpers - 2) : p.attn_grid;
+        // with helpers the bound's last tile and its helper are extra jobs of existing workgroups
+        p.attn_grid = 8 * p.gpx * (p.helpers ? p.tiles + p.helpers - 2 : p.tiles);
+        p.attn_first = p.attn_grid;
         // fused append: a few dozen workgroups, each copying every 64th row of the chunk
         // (every workgroup of this kernel occupies a whole CU: in a launch that splits key ranges only
         // the CUs its attention workgroups leave free take append workgroups right away)

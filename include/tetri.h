@@ -10,6 +10,9 @@
  *   - Sec. 2.1: prefill of a causal LLM produces the KV cache, so each chunk attends to all
  *     earlier tokens of its own request(s) and to itself;
  *   - Sec. 3.4 / Sec. 5: the KV cache is managed in pages.
+ * and the steps that follow it on the same pages: the prefill scheduler's ordering (Sec. 3.3.2), the export /
+ * import of a request's KV cache between the instances (Sec. 3.3.4), the decode instance's attention
+ * iteration (Sec. 2.1, Sec. 3.4), and an FP8 variant of the decode-side cache (an extension of this build).
  *
  * Conventions shared by every entry point
  *   - Plain C, no exceptions, no aborts: every call returns a tetri_status (or a count that

@@ -574,23 +574,41 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // exponentiating and rounding this block's weights on the VALU against the reference exponent
         // m the row already has; then the PV product with the V fragments in vf.
         auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, const s16x8 (&vf)[2 * DBLK]) {
-            __builtin_amdgcn_sched_barrier(0);
-            s_next = qk(kf);
             bf16x8 pf[2];
-            float l_blk = weights(s_cur, pf);
-            // wanted order: one MFMA of the score chain, then its share of the VALU operations, 8 times
+            float l_blk;
+            if constexpr (KS == 1) {
+                // Four-wavefront workgroups run two to a compute unit, so the two wavefronts of a SIMD belong
+                // to different workgroups and are not held in step by a common barrier.  Here the block has a
+                // VALU phase (the weights) and an MFMA phase at raised wavefront priority: one wavefront's
+                // matrix instructions go out back to back while the other, in its VALU phase, takes the issue
+                // slots in between (measured: +7 to +13 % on launches with two workgroups per compute unit; for
+                // eight-wavefront workgroups, whose SIMD partners meet at every barrier, no gain).
+                __builtin_amdgcn_sched_barrier(0);
+                l_blk = weights(s_cur, pf);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_pending(1);
+                __builtin_amdgcn_s_setprio(3);
+                s_next = qk(kf);
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                __builtin_amdgcn_sched_barrier(0);
+                s_next = qk(kf);
+                l_blk = weights(s_cur, pf);
+                // wanted order: one MFMA of the score chain, then its share of the VALU operations, 8 times
 #pragma unroll
-            for (int g = 0; g < KSTEPS; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
+                for (int g = 0; g < KSTEPS; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                issue_pending(1);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            issue_pending(1);
             // m is only a reference point, not the exact row maximum: any value keeps the result exact
             // as long as the weights stay in range.  Only when a lane's weights of this block sum to
             // more than 2^16 (or overflowed: first block, or scores far above anything seen before) is
             // m raised to the true maximum, O and the row sum rescaled in place, and the weights
-            // recomputed.  The two half-waves of a row take the same decision.
+            // recomputed.  The two half-waves of a row take the same decision.  (In the
+            // phased order the vote sits behind the score MFMAs, where its operands are long there.)
             if (__builtin_amdgcn_ballot_w64(!(l_blk <= 65536.0f)) != 0) {
                 float mx = s_cur[0] * c;
 #pragma unroll
@@ -616,7 +634,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
-                if (j == 0) issue_pending(2);
+                if (KS != 1 && j == 0) issue_pending(2);
+            }
+            if constexpr (KS == 1) {
+                __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_pending(2);
             }
         };
         // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false

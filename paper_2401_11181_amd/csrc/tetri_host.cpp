@@ -567,8 +567,16 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     p.kv_magic = magic((uint32_t)(p.g / p.hpw));
     if ((uint64_t)p.attn_grid * (uint64_t)(p.tiles + p.helpers) >= 0x100000000ull)
         return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
+    // Workgroup size of the shared-tile kernel.  A full chunk has at least C / (rows of a tile) tiles per head
+    // group; when that alone gives two workgroups per compute unit, four-wavefront workgroups (two to a CU, their
+    // barriers independent of each other) run the block loop 4-15 % faster than eight-wavefront ones; on smaller
+    // launches the eight-wavefront workgroup, which puts twice the wavefronts on its tile's CU, is the better one.
+    int key_parts = h->attn_variant == 1 ? 1 : 2;
+    if (h->attn_variant == 0 && !split && p.helpers == 0 &&
+        (int64_t)(p.C / (32 * p.rb)) * p.groups >= 2 * (int64_t)std::max(h->num_cus, 1))
+        key_parts = 1;
     hipError_t e = split ? tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream))
-                         : tetri_launch_attn(h, p, h->attn_variant == 1 ? 1 : 2, static_cast<hipStream_t>(stream));
+                         : tetri_launch_attn(h, p, key_parts, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;
 }

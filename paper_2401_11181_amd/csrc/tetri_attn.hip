@@ -10,6 +10,9 @@
 //     (32-row blocks).  With KS = 2 a CU holds 8 wavefronts, two per SIMD, so one wavefront's
 //     softmax (VALU) overlaps the other's MFMA, while every K/V byte brought into LDS still
 //     serves 128 query rows.  The KS partial results are merged once through LDS at the end.
+//     With KS = 1 a workgroup has 4 wavefronts and half the LDS, two workgroups share a CU and the
+//     two wavefronts of a SIMD belong to different workgroups (no common barrier); the library
+//     uses it for launches with at least two workgroups per CU (see softmax_pv for its schedule).
 //   * A stage is 64*KS keys of K and V.  Stages go from HBM/L2 straight into LDS with
 //     global_load_lds_dwordx4 (no register staging), double buffered: the loads of stage i+1 are
 //     in flight while stage i is consumed; one workgroup barrier per stage.  The 16 key rows a

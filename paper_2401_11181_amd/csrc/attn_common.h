@@ -13,8 +13,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_cvoid;
 
 constexpr int kPage = 16;     // tokens per KV page
 constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
@@ -90,12 +88,6 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
-// Same, with the global address given as a wave-uniform 64-bit base plus a per-lane 32-bit byte
-// offset (no per-lane 64-bit address arithmetic).
-__device__ __forceinline__ void dma16_sbase(const void *sbase, uint32_t voff, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
-}
 // A group of such loads that share one scalar base and one LDS base: instruction i moves
 // 16 bytes per lane from sbase + voff_i + 1024*i to LDS byte lds_base + 1024*i + 16*lane.  The
 // instruction's immediate offset advances the global and the LDS address alike, so M0 is written
@@ -113,11 +105,6 @@ __device__ __forceinline__ void dma16_group2(const void *sbase, uint32_t v0, uin
     asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, %2\n\t"
                  "global_load_lds_dwordx4 %1, %2 offset:1024" ::"v"(v0), "v"(v1), "s"(sbase), "s"(lds_base) : "memory", "m0");
-}
-// One load of such a group on its own (IMM = 1024 * i).
-template <int IMM> __device__ __forceinline__ void dma16_imm(const void *sbase, uint32_t voff, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(IMM) : "memory", "m0");
 }
 // Accesses that are coherent across the whole device by themselves (cache policy sc1: they are
 // served by the memory side, not by an XCD's L2), for data handed from one workgroup to another

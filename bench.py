@@ -30,7 +30,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
 # plain copy of known size (figures and commands: profiles/attn_tile_kernel_opt13b_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {("opt13b", "fused"): 76.3e6}
+MEASURED_TRAFFIC_BYTES = {("opt13b", "fused"): 76.5e6}
 
 
 def layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev):

@@ -200,6 +200,8 @@ def main():
     R, reps = 10, max(3, min(20, args.steps // 10))
     stream = torch.cuda.current_stream()
 
+    spread = []                                     # (p10, p90) of every group_time call, in call order
+
     def group_time(launch):
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
@@ -215,6 +217,7 @@ def main():
             e1.record(stream)
             e1.synchronize()
             times.append(e0.elapsed_time(e1) / R)
+        spread.append((float(np.percentile(times, 10)), float(np.percentile(times, 90))))
         return float(np.median(times))
 
     torch.cuda.synchronize()
@@ -269,6 +272,8 @@ def main():
         },
         "per_chunk": {
             "attn_ms_median": [round(float(x), 5) for x in attn_med],
+            "attn_ms_p10": [round(spread[i][0], 5) for i in range(len(attn_med))],
+            "attn_ms_p90": [round(spread[i][1], 5) for i in range(len(attn_med))],
             "attn_tflops": [round(flops[c] / (float(attn_med[c]) * 1e-3) / 1e12, 2) for c in range(len(attn_med))],
             "append_ms_median": [round(float(x), 5) for x in app_med],
         },

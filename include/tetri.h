@@ -336,7 +336,7 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  * Kernel-variant selection for measurements and tests.  Known keys:
  *   "attn_variant"      0 = the library chooses the kernel (8-wavefront workgroups; 4-wavefront ones, two to a
  *                       compute unit, when a full chunk alone gives two workgroups per compute unit), 1 / 2 =
- *                       shared-tile kernel with 4- / 8-wavefront workgroups, 3 = key-split kernel;
+ *                       shared-tile kernel with 4- / 8-wavefront workgroups;
  *   "split_keys"        1 (default) = a launch whose row tiles would occupy at most two thirds of the
  *                       device's compute units hands the last third of long key ranges to extra
  *                       workgroups (the two parts of a tile meet in scratch memory the handle owns:

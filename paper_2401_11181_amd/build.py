@@ -7,8 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtetri.so")
-SOURCES = ["tetri_host.cpp", "tetri_append.hip", "tetri_kv_transfer.hip", "tetri_decode.hip", "tetri_attn.hip", "tetri_attn_split.hip"]
-HEADERS = [os.path.join(CSRC, "tetri_internal.h"), os.path.join(CSRC, "attn_common.h"), os.path.join(ROOT, "include", "tetri.h")]
+SOURCES = ["tetri_host.cpp", "tetri_plan.cpp", "tetri_append.hip", "tetri_kv_transfer.hip", "tetri_decode.hip", "tetri_attn.hip"]
+HEADERS = [os.path.join(CSRC, "tetri_internal.h"), os.path.join(CSRC, "tetri_plan.h"), os.path.join(CSRC, "attn_common.h"), os.path.join(ROOT, "include", "tetri.h")]
 
 # packed-fp32 instructions are switched off for all device code
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

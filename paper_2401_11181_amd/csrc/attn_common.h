@@ -17,18 +17,9 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 constexpr int kPage = 16;     // tokens per KV page
 constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
 
-// Optional timeline instrumentation (only in builds with -DTETRI_TRACE, never in the product
-// library): lane 0 of every wavefront stores the 100 MHz constant clock at numbered points.
-#ifdef TETRI_TRACE
-constexpr int kTraceMarks = 8, kTraceWaves = 8, kTraceBlocks = 4096;
-static __device__ unsigned long long g_trace[kTraceBlocks * kTraceWaves * kTraceMarks];
-#define TETRI_MARK(i_)                                                                                  \
-    do {                                                                                                \
-        if ((threadIdx.x & 63) == 0 && blockIdx.x < tetri_dev::kTraceBlocks)                            \
-            tetri_dev::g_trace[(blockIdx.x * tetri_dev::kTraceWaves + (threadIdx.x >> 6)) * tetri_dev::kTraceMarks + (i_)] = \
-                __builtin_amdgcn_s_memrealtime();                                                       \
-    } while (0)
-#else
+// Numbered points of the kernels' timelines.  The library compiles them to nothing; a measurement
+// build may define the macro before this header (e.g. to store a clock value per wavefront).
+#ifndef TETRI_MARK
 #define TETRI_MARK(i_) do { } while (0)
 #endif
 

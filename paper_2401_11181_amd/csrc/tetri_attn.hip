@@ -895,15 +895,6 @@ hipError_t launch(const AttnParams &p, hipStream_t stream)
 
 }  // namespace
 
-#ifdef TETRI_TRACE
-// Copies the timeline marks of the last launches to the host (trace builds only).
-extern "C" TETRI_API int tetri_debug_trace(unsigned long long *host, size_t count)
-{
-    const size_t all = (size_t)kTraceBlocks * kTraceWaves * kTraceMarks;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * (count < all ? count : all));
-}
-#endif
-
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream)
 {
     if (h->cfg.head_dim == 128)

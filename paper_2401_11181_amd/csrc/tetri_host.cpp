@@ -1,5 +1,5 @@
-// Host layer of libtetri: handle, argument checks, the chunk packer and the debug validator.
-// TetriInfer Sec. 3.3.3 "Chunked Prefill" is the source of the packing rule.
+// Host layer of libtetri: handle, argument checks, launch shapes and the debug validator.
+// (The chunk packer and the scheduler are in tetri_plan.cpp, which needs no HIP.)
 #include <algorithm>
 #include <cmath>
 #include <cstdarg>
@@ -9,10 +9,9 @@
 #include <vector>
 
 #include "tetri_internal.h"
+#include "tetri_plan.h"
 
 namespace {
-
-thread_local std::string g_thread_err;
 
 tetri_status fail(tetri_ctx *h, tetri_status st, const char *fmt, ...)
 {
@@ -21,7 +20,7 @@ tetri_status fail(tetri_ctx *h, tetri_status st, const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(buf, sizeof buf, fmt, ap);
     va_end(ap);
-    if (h) h->err = buf; else g_thread_err = buf;
+    if (h) h->err = buf; else tetri_set_thread_error(buf);
     return st;
 }
 
@@ -49,7 +48,7 @@ int32_t tetri_abi_version(void) { return 1; }
 
 const char *tetri_last_error(const tetri_ctx *ctx)
 {
-    return ctx ? ctx->err.c_str() : g_thread_err.c_str();
+    return ctx ? ctx->err.c_str() : tetri_thread_error();
 }
 
 tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
@@ -140,150 +139,11 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         return TETRI_OK;
     }
     if (std::strcmp(key, "attn_variant") == 0) {
-        if (value < 0 || value > 3) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
+        if (value < 0 || value > 2) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: attn_variant=%d unknown", value);
         ctx->attn_variant = value;
         return TETRI_OK;
     }
     return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: unknown key '%s'", key);
-}
-
-int32_t tetri_pack_chunks(const int32_t *prompt_lens, int32_t n_prompts, const int32_t *order, int32_t n_order,
-                          int32_t chunk_size, tetri_segment *segs, int32_t seg_capacity,
-                          int32_t *chunk_seg_offsets, int32_t chunk_capacity, int32_t *n_segs_out)
-{
-    if (!prompt_lens || n_prompts < 0 || n_order < 0)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: null prompt_lens or negative count");
-    if (chunk_size < 1) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: chunk_size=%d", chunk_size);
-    if (!order && n_order > n_prompts)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: n_order=%d exceeds n_prompts=%d", n_order, n_prompts);
-    const bool query = (segs == nullptr && chunk_seg_offsets == nullptr);
-    if (!query && (!segs || !chunk_seg_offsets))
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: segs and chunk_seg_offsets must both be given or both be null");
-    std::vector<char> seen(order ? (size_t)n_prompts : 0, 0);
-    int64_t n_chunks = 0, n_segs = 0;
-    int32_t room = 0;                      // free rows left in the chunk being filled
-    for (int32_t i = 0; i < n_order; ++i) {
-        const int32_t req = order ? order[i] : i;
-        if (req < 0 || req >= n_prompts)
-            return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: order[%d]=%d out of range", i, req);
-        if (order) {
-            if (seen[req]) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: request %d scheduled twice", req);
-            seen[req] = 1;
-        }
-        const int32_t len = prompt_lens[req];
-        if (len < 0) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: prompt_lens[%d]=%d", req, len);
-        int32_t done = 0;
-        while (done < len) {
-            if (room == 0) {               // open the next chunk
-                if (!query) {
-                    if (n_chunks >= chunk_capacity)
-                        return fail(nullptr, TETRI_ERR_NOMEM, "tetri_pack_chunks: chunk_capacity=%d too small", chunk_capacity);
-                    chunk_seg_offsets[n_chunks] = (int32_t)n_segs;
-                }
-                ++n_chunks;
-                room = chunk_size;
-            }
-            const int32_t take = (len - done < room) ? len - done : room;
-            if (!query) {
-                if (n_segs >= seg_capacity)
-                    return fail(nullptr, TETRI_ERR_NOMEM, "tetri_pack_chunks: seg_capacity=%d too small", seg_capacity);
-                segs[n_segs].req = req;
-                segs[n_segs].start = done;
-                segs[n_segs].len = take;
-            }
-            ++n_segs;
-            done += take;
-            room -= take;
-        }
-    }
-    if (n_chunks > INT32_MAX || n_segs > INT32_MAX)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_pack_chunks: plan too large");
-    if (!query) chunk_seg_offsets[n_chunks] = (int32_t)n_segs;
-    if (n_segs_out) *n_segs_out = (int32_t)n_segs;
-    return (int32_t)n_chunks;
-}
-
-tetri_status tetri_schedule(const int32_t *prompt_lens, int32_t n, int32_t policy, int32_t sched_batch, int32_t *order_out)
-{
-    if (!prompt_lens || !order_out || n < 0)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: null pointer or negative count");
-    if (policy != TETRI_FCFS && policy != TETRI_SJF && policy != TETRI_LJF)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: unknown policy %d", policy);
-    for (int32_t i = 0; i < n; ++i) {
-        if (prompt_lens[i] < 0) return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_schedule: prompt_lens[%d]=%d", i, prompt_lens[i]);
-        order_out[i] = i;
-    }
-    if (policy == TETRI_FCFS) return TETRI_OK;
-    const int32_t group = sched_batch > 0 ? sched_batch : (n > 0 ? n : 1);
-    for (int32_t b = 0; b < n; b += group) {
-        int32_t *first = order_out + b, *last = order_out + (b + group < n ? b + group : n);
-        if (policy == TETRI_SJF)
-            std::stable_sort(first, last, [&](int32_t x, int32_t y) { return prompt_lens[x] < prompt_lens[y]; });
-        else
-            std::stable_sort(first, last, [&](int32_t x, int32_t y) { return prompt_lens[x] > prompt_lens[y]; });
-    }
-    return TETRI_OK;
-}
-
-tetri_status tetri_chunk_metadata(const tetri_segment *segs, int32_t num_segs, const int32_t *req_block_tables,
-                                  int32_t n_prompts, int32_t max_blocks_per_seq,
-                                  int32_t *cu_out, int32_t *ctx_out, int32_t *block_table_out)
-{
-    if (!segs || !req_block_tables || !cu_out || !ctx_out || !block_table_out || num_segs < 1 || max_blocks_per_seq < 1)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_chunk_metadata: null argument or empty chunk");
-    cu_out[0] = 0;
-    for (int32_t s = 0; s < num_segs; ++s) {
-        if (segs[s].req < 0 || segs[s].req >= n_prompts || segs[s].len <= 0 || segs[s].start < 0)
-            return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_chunk_metadata: segment %d is malformed", s);
-        cu_out[s + 1] = cu_out[s] + segs[s].len;
-        ctx_out[s] = segs[s].start;
-        std::memcpy(block_table_out + (size_t)s * max_blocks_per_seq,
-                    req_block_tables + (size_t)segs[s].req * max_blocks_per_seq,
-                    sizeof(int32_t) * (size_t)max_blocks_per_seq);
-    }
-    return TETRI_OK;
-}
-
-int32_t tetri_plan_metadata(const int32_t *prompt_lens, int32_t n_prompts, const int32_t *order, int32_t n_order,
-                            int32_t chunk_size, const int32_t *req_block_tables, int32_t max_blocks,
-                            int32_t *meta_out, int64_t meta_capacity, int32_t *layout_out, int32_t chunk_capacity,
-                            int64_t *meta_len_out)
-{
-    if (!req_block_tables || max_blocks < 1)
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_plan_metadata: null block tables or max_blocks_per_seq < 1");
-    const bool query = (meta_out == nullptr && layout_out == nullptr);
-    if (!query && (!meta_out || !layout_out))
-        return fail(nullptr, TETRI_ERR_INVALID_ARG, "tetri_plan_metadata: meta_out and layout_out must both be given or both be null");
-    int32_t n_segs = 0;
-    const int32_t n_chunks = tetri_pack_chunks(prompt_lens, n_prompts, order, n_order, chunk_size, nullptr, 0, nullptr, 0, &n_segs);
-    if (n_chunks < 0) return n_chunks;
-    thread_local std::vector<tetri_segment> segs;
-    thread_local std::vector<int32_t> offs;
-    segs.resize((size_t)n_segs + 1);
-    offs.resize((size_t)n_chunks + 1);
-    int32_t rc = tetri_pack_chunks(prompt_lens, n_prompts, order, n_order, chunk_size, segs.data(), n_segs, offs.data(), n_chunks, nullptr);
-    if (rc < 0) return rc;
-    if (!query && n_chunks > chunk_capacity)
-        return fail(nullptr, TETRI_ERR_NOMEM, "tetri_plan_metadata: chunk_capacity=%d too small for %d chunks", chunk_capacity, n_chunks);
-    auto up4 = [](int64_t x) { return (x + 3) / 4 * 4; };
-    int64_t at = 0;
-    for (int32_t c = 0; c < n_chunks; ++c) {
-        const int32_t S = offs[c + 1] - offs[c];
-        const int64_t o_cu = at, o_ctx = o_cu + up4(S + 1), o_bt = o_ctx + up4(S);
-        at = o_bt + up4((int64_t)S * max_blocks);
-        if (query) continue;
-        if (at > meta_capacity || at > INT32_MAX)
-            return fail(nullptr, TETRI_ERR_NOMEM, "tetri_plan_metadata: meta_capacity=%lld too small", (long long)meta_capacity);
-        layout_out[4 * c + 0] = (int32_t)o_cu;
-        layout_out[4 * c + 1] = (int32_t)o_ctx;
-        layout_out[4 * c + 2] = (int32_t)o_bt;
-        layout_out[4 * c + 3] = S;
-        tetri_status st = tetri_chunk_metadata(segs.data() + offs[c], S, req_block_tables, n_prompts, max_blocks,
-                                               meta_out + o_cu, meta_out + o_ctx, meta_out + o_bt);
-        if (st != TETRI_OK) return st;
-    }
-    if (meta_len_out) *meta_len_out = at;
-    return n_chunks;
 }
 
 static tetri_status check_common(tetri_ctx *h, const char *fn, const void *const *ptrs, const char *const *names, int n,
@@ -509,17 +369,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     // while masked scores (-inf) still map to weight 0
     p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     p.neg = scale < 0.f;
-    const bool split = h->attn_variant == 3 && !kv_pages_w;
-    if (split) {
-        // key-split kernel: one workgroup per (head, 32-row block)
-        p.hpw = 1; p.rb = 1;
-        p.tiles = tile_bound(p.C, p.S, 32);
-        p.attn_grid = (p.tiles * p.Hq + 7) / 8 * 8;
-        p.append_blocks = 0;
-        p.helpers = 0;
-        p.gpx = 1;
-        p.attn_first = p.attn_grid;
-    } else {
+    {
         wave_grouping(p.g, &p.hpw, &p.rb);
         p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
         // A launch whose tiles would occupy at most two thirds of the CUs gets one more workgroup
@@ -572,11 +422,10 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     // barriers independent of each other) run the block loop 4-15 % faster than eight-wavefront ones; on smaller
     // launches the eight-wavefront workgroup, which puts twice the wavefronts on its tile's CU, is the better one.
     int key_parts = h->attn_variant == 1 ? 1 : 2;
-    if (h->attn_variant == 0 && !split && p.helpers == 0 &&
+    if (h->attn_variant == 0 && p.helpers == 0 &&
         (int64_t)(p.C / (32 * p.rb)) * p.groups >= 2 * (int64_t)std::max(h->num_cus, 1))
         key_parts = 1;
-    hipError_t e = split ? tetri_launch_attn_split(h, p, static_cast<hipStream_t>(stream))
-                         : tetri_launch_attn(h, p, key_parts, static_cast<hipStream_t>(stream));
+    hipError_t e = tetri_launch_attn(h, p, key_parts, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     return TETRI_OK;
 }

@@ -9,7 +9,7 @@
 struct tetri_ctx {
     tetri_config cfg;
     std::string err;
-    int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts, 3 = key-split kernel
+    int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts
     int split_keys = 1;     // 1 = launches that would leave a third of the CUs idle split the key ranges of their tiles
     int split_min_stages = 8;   // ... those of at least this many stages
     int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
@@ -86,7 +86,6 @@ struct DecodeParams {
 };
 
 hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
-hipError_t tetri_launch_attn_split(const tetri_ctx *h, const AttnParams &p, hipStream_t stream);
 hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t row_units, int32_t tiles,
                                     bool to_pool, hipStream_t stream);
 hipError_t tetri_launch_kv_export_fp8(const tetri_ctx *h, const TransferParams &p, int32_t tiles, hipStream_t stream);

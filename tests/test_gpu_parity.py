@@ -13,13 +13,13 @@ import gpu_common as gc
 
 pytestmark = pytest.mark.gpu
 
-# attention kernel variants: 0 = library's choice, 1 / 2 = shared-tile kernel with 4 / 2 wavefronts,
-# 3 = key-split kernel; 10 / 11 = kernels 0 / 1 handing the last third of every key range of two or
+# attention kernel variants: 0 = library's choice, 1 / 2 = shared-tile kernel with 4 / 8 wavefronts;
+# 10 / 11 = kernels 0 / 1 handing the last third of every key range of two or
 # more stages to a second workgroup (13: half of it), 12 = kernel 0 never doing so.  Every variant must meet the same bar.
-VARIANTS = [0, 1, 2, 3, 10, 11, 12, 13]
+VARIANTS = [0, 1, 2, 10, 11, 12, 13]
 
 
-@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "split", "handover", "handover4", "whole", "handover-half"])
+@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "handover", "handover4", "whole", "handover-half"])
 def variant(request):
     return request.param
 
@@ -75,14 +75,16 @@ def test_append_before_attention_gives_same_result(oracle, variant):
     assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
 
 
-@pytest.mark.parametrize("name", ["mid-page-starts", "ragged-tiles", "gqa4", "one-token-segments", "partial-last-chunk"])
-def test_fused_attention_append_equals_two_calls(oracle, name):
-    """tetri_chunk_prefill_attn_append == tetri_chunk_prefill_attn then tetri_kv_append, bit for bit."""
+@pytest.mark.parametrize("fused_variant", [0, 1, 2], ids=["auto", "tile4", "tile2"])
+@pytest.mark.parametrize("name", ["mid-page-starts", "ragged-tiles", "gqa4", "one-token-segments", "partial-last-chunk", "many-tiles"])
+def test_fused_attention_append_equals_two_calls(oracle, name, fused_variant):
+    """tetri_chunk_prefill_attn_append == tetri_chunk_prefill_attn then tetri_kv_append, bit for bit, also with the
+    4-wavefront workgroups (whose append workgroups have 256 threads) the library picks for large launches."""
     lens, chunk, hq, hkv, d = CASES[name]
     w = synth.small(name, lens, chunk, hq, hkv, d, seed=140)
     qs, ks, vs, tables = gc.workload_tensors(w)
-    a, pool_a, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables)
-    b, pool_b, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, fused=True)
+    a, pool_a, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, variant=fused_variant)
+    b, pool_b, _, _ = gc.gpu_prefill(w, qs, ks, vs, tables, fused=True, variant=fused_variant)
     for x, y in zip(a, b):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
     assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))

@@ -278,6 +278,26 @@ TETRI_API tetri_status tetri_decode_attn(tetri_ctx *ctx, const void *q, const vo
                                          int32_t num_reqs, int32_t max_ctx_len, float scale, void *out, void *stream);
 
 /*
+ * tetri_decode_attn for callers that cannot allocate device memory or hold an allocation: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same function and
+ * same kernels as tetri_decode_attn; the only difference is where the parts of split requests are kept: not
+ * in memory the handle allocated but in a static device array of the library, 8 MiB on every device the
+ * library runs on, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine); the array's address on the handle's device was looked up by tetri_create.
+ * Limit: num_reqs * num_q_heads * (head_dim + 2) * 4 bytes * 2 must fit the array (two parts per request and
+ * head; 8066 (request, head) pairs at head_dim 128), else TETRI_ERR_INVALID_ARG and nothing is launched;
+ * within the limit the keys of a request are split as far as the array reaches, so the split (and with it
+ * the rounding, not the function) may differ from tetri_decode_attn's; with the same "decode_parts" the
+ * two calls give the same bits.
+ * Every call on a device shares that device's array, which keeps the last call's contents (every part is
+ * written before it is read, nothing has to start at zero): calls that overlap in time on one device, on
+ * any handles or streams, race.
+ */
+TETRI_API tetri_status tetri_decode_attn_static(tetri_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                                                const void *kv_pages, const int32_t *block_table, const int32_t *ctx_lens,
+                                                int32_t num_reqs, int32_t max_ctx_len, float scale, void *out, void *stream);
+
+/*
  * The decode iteration and the caching of its new tokens in ONE launch (Sec. 2.1: every decode
  * iteration extends the KV cache by one token).  Same `out`, bit for bit, as tetri_decode_attn, and the
  * same pool as tetri_kv_append with cu_chunk_q_lens = 0, 1, ..., num_reqs afterwards: k_new[b] / v_new[b]

@@ -29,6 +29,8 @@
 // the 16-bit path.  The scales are not applied per element: the K scale multiplies the scores of cached
 // keys, the V scale the finished output; the new token, which is not quantised, gets the inverse factors
 // on its score and on its weight in the last step.
+#include <mutex>
+
 #include "attn_common.h"
 
 namespace {
@@ -412,6 +414,35 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p)
 }
 
 }  // namespace
+
+// Scratch memory of tetri_decode_attn_static: the parts of split requests, in an array that is part
+// of the loaded code object instead of an allocation (8 MiB on every device the library runs on,
+// held until the process ends).  On the host the array's name is only a stand-in for the symbol: the
+// device address is looked up once per device, with that device current, and only that address
+// is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticScratchBytes];
+
+hipError_t tetri_decode_static_scratch(float **ptr, size_t *bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *per_device[kMaxDevices];               // zero until the device's address is known
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = static_cast<float *>(per_device[dev]);
+    *bytes = kDecodeStaticScratchBytes;
+    return hipSuccess;
+}
 
 hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStream_t stream)
 {

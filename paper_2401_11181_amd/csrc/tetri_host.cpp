@@ -93,6 +93,12 @@ tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
         tetri_destroy(h);
         return fail(nullptr, TETRI_ERR_HIP, "tetri_create: scratch memory: %s", hipGetErrorString(e));
     }
+    // the static scratch array of tetri_decode_attn_static: its address on this device, looked up here so that the
+    // entry point itself makes no runtime call besides the launch
+    if ((e = tetri_decode_static_scratch(&h->static_scratch, &h->static_scratch_bytes)) != hipSuccess) {
+        tetri_destroy(h);
+        return fail(nullptr, TETRI_ERR_HIP, "tetri_create: static scratch array: %s", hipGetErrorString(e));
+    }
     *out = h;
     return TETRI_OK;
 }
@@ -258,7 +264,8 @@ tetri_status tetri_kv_import(tetri_ctx *h, const void *buf, const int32_t *block
 static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
                                   const void *kv_pages, void *kv_pages_w, const int32_t *block_table,
                                   const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len, float scale, void *out,
-                                  void *stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f)
+                                  void *stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f,
+                                  bool static_scratch = false)
 {
     if (!h) return fail(nullptr, TETRI_ERR_INVALID_ARG, "%s: null handle", fn);
     const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
@@ -289,7 +296,7 @@ static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, c
     p.bt = block_table; p.ctx = ctx_lens;
     p.out = static_cast<uint16_t *>(out);
     p.pages_w = static_cast<uint16_t *>(kv_pages_w);
-    p.partial = reinterpret_cast<float *>(h->scratch);
+    p.partial = static_scratch ? h->static_scratch : reinterpret_cast<float *>(h->scratch);
     p.B = num_reqs; p.Hq = cfg.num_q_heads; p.Hkv = cfg.num_kv_heads; p.g = p.Hq / p.Hkv;
     p.max_blocks = cfg.max_blocks_per_seq;
     p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
@@ -306,7 +313,12 @@ static tetri_status decode_common(const char *fn, tetri_ctx *h, const void *q, c
     const int64_t pairs = (int64_t)num_reqs * p.Hkv;
     const int64_t steps = ((int64_t)max_ctx_len + 32) / 32;
     const int64_t per_part = (int64_t)num_reqs * p.Hq * (cfg.head_dim + 2) * 4;        // scratch bytes of one part
-    const int64_t fit = (int64_t)(2 * h->scratch_units * h->unit_bytes) / per_part;
+    const int64_t room = static_scratch ? (int64_t)h->static_scratch_bytes : (int64_t)(2 * h->scratch_units * h->unit_bytes);
+    if (static_scratch && 2 * per_part > room)
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: num_reqs x num_q_heads = %lld exceeds what the static scratch array of %lld bytes "
+                    "holds (two parts of head_dim + 2 floats per request and head: at most %lld)", fn,
+                    (long long)num_reqs * cfg.num_q_heads, (long long)room, (long long)(room / (2 * (cfg.head_dim + 2) * 4)));
+    const int64_t fit = room / per_part;
     int64_t parts = (4 * (int64_t)std::max(h->num_cus, 1) + pairs - 1) / pairs;
     parts = std::min(parts, std::max<int64_t>(1, steps / 8));
     if (h->decode_parts > 0) parts = h->decode_parts;
@@ -324,6 +336,14 @@ tetri_status tetri_decode_attn(tetri_ctx *h, const void *q, const void *k_new, c
 {
     return decode_common("tetri_decode_attn", h, q, k_new, v_new, kv_pages, nullptr, block_table, ctx_lens, num_reqs,
                          max_ctx_len, scale, out, stream);
+}
+
+tetri_status tetri_decode_attn_static(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                                      const int32_t *block_table, const int32_t *ctx_lens, int32_t num_reqs, int32_t max_ctx_len,
+                                      float scale, void *out, void *stream)
+{
+    return decode_common("tetri_decode_attn_static", h, q, k_new, v_new, kv_pages, nullptr, block_table, ctx_lens, num_reqs,
+                         max_ctx_len, scale, out, stream, false, 1.f, 1.f, true);
 }
 
 tetri_status tetri_decode_attn_fp8(tetri_ctx *h, const void *q, const void *k_new, const void *v_new, void *kv_pages_fp8,

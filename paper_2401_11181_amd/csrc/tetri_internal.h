@@ -21,7 +21,12 @@ struct tetri_ctx {
     char *scratch = nullptr;        // partial results of split tiles: 2 pieces x scratch_units units
     int32_t *counters = nullptr;    // scratch_units arrival counters, zero between launches
     size_t scratch_units = 0, unit_bytes = 0;
+    float *static_scratch = nullptr;    // this device's address of the library's static scratch array (decode parts)
+    size_t static_scratch_bytes = 0;
 };
+
+// Size of the static device array behind tetri_decode_attn_static.
+constexpr size_t kDecodeStaticScratchBytes = (size_t)8 << 20;
 
 // Launch parameters of the attention kernels (passed by value).
 struct AttnParams {
@@ -90,4 +95,6 @@ hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p,
                                     bool to_pool, hipStream_t stream);
 hipError_t tetri_launch_kv_export_fp8(const tetri_ctx *h, const TransferParams &p, int32_t tiles, hipStream_t stream);
 hipError_t tetri_launch_decode(const tetri_ctx *h, const DecodeParams &p, hipStream_t stream);
+// Device address (on the current device) and size of the static scratch array of the decode kernels.
+hipError_t tetri_decode_static_scratch(float **ptr, size_t *bytes);
 hipError_t tetri_launch_append(const tetri_ctx *h, const AppendParams &p, int32_t chunk_rows, hipStream_t stream);

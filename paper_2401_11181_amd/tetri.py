@@ -75,6 +75,8 @@ def lib():
         L.tetri_chunk_prefill_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
         L.tetri_decode_attn.restype = i32
         L.tetri_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
+        L.tetri_decode_attn_static.restype = i32
+        L.tetri_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.tetri_decode_attn_append.restype = i32
         L.tetri_decode_attn_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.tetri_kv_export_fp8.restype = i32
@@ -247,6 +249,12 @@ class Tetri:
         self._check(lib().tetri_decode_attn(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
                                             _ptr(block_table), _ptr(ctx_lens), int(num_reqs), int(max_ctx_len),
                                             float(scale), _ptr(out), _stream(stream)))
+
+    def tetri_decode_attn_static(self, q, k_new, v_new, kv_pages, block_table, ctx_lens, num_reqs, max_ctx_len, scale, out,
+                                 stream=None):
+        self._check(lib().tetri_decode_attn_static(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages),
+                                                   _ptr(block_table), _ptr(ctx_lens), int(num_reqs), int(max_ctx_len),
+                                                   float(scale), _ptr(out), _stream(stream)))
 
     def tetri_decode_attn_append(self, q, k_new, v_new, kv_pages, block_table, ctx_lens, num_reqs, max_ctx_len, scale,
                                  out, stream=None):

@@ -100,6 +100,8 @@ def main():
                     help="finish with one 256 MiB device-to-device copy (known traffic, to calibrate HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="tetri_set_option on the benchmark's handle (measurement only), e.g. --opt split_keys=0")
     ap.add_argument("--policy", default=None, choices=["fcfs", "sjf", "ljf"],
                     help="order the workload's requests with tetri_schedule (Sec. 3.3.2) before packing")
     ap.add_argument("--sched-batch", type=int, default=0, help="PrefillSchedBatch: requests per sorted group (0: all)")
@@ -147,6 +149,9 @@ def main():
                            use_graph=(args.mode == "graph"), fused=not args.two_launches, export=args.export)
     if args.variant is not None:
         pipe.handle.tetri_set_option("attn_variant", args.variant)
+    for kv in args.opt:
+        key, value = kv.split("=")
+        pipe.handle.tetri_set_option(key, int(value))
     nC, C = pipe.n_chunks, w.chunk_size
 
     # inputs: what the QKV projection of each chunk would hand to this path, resident in HBM
@@ -297,6 +302,9 @@ def main():
                                  use_graph=(args.mode == "graph"), fused=not args.two_launches)
             if args.variant is not None:
                 pp.handle.tetri_set_option("attn_variant", args.variant)
+            for kv in args.opt:
+                key, value = kv.split("=")
+                pp.handle.tetri_set_option(key, int(value))
             bufs = (q.clone(), k.clone(), v.clone(), pool.clone(), torch.zeros_like(out))
             pp.bind(*bufs)
             keep.append(bufs)

@@ -87,8 +87,15 @@ typedef struct {
 
 /*
  * Create / destroy a handle carrying the static shape.  The handle owns a fixed amount of device
- * scratch memory (about 33 MB on a 256-CU device, allocated here, freed by tetri_destroy) on the
+ * scratch memory (about 34 MB on a 256-CU device, allocated here, freed by tetri_destroy) on the
  * device that is current at creation; launching calls must be made with that device current.
+ * tetri_chunk_prefill_attn / _attn_append (launches small enough to be divided over the compute units by
+ * stages rather than by row tiles) and tetri_decode_attn keep partial results there: such launches on one
+ * handle must not overlap in time; use one handle per stream that runs concurrently.  The attention calls
+ * return TETRI_ERR_INVALID_ARG when the handle's previous such launch went to another stream and that stream
+ * still has work pending (synchronise the two streams, or use a handle each); the
+ * arrival counters they use are zeroed for each launch by the launch before it (and by tetri_create), so
+ * no state survives from one launch to the next.
  * tetri_create checks the configuration (TETRI_ERR_UNSUPPORTED / TETRI_ERR_INVALID_ARG) and
  * that a HIP device is usable (TETRI_ERR_HIP) and stores the handle in *out.
  * A handle must not be used by two threads at once.
@@ -354,18 +361,17 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
 
 /*
  * Kernel-variant selection for measurements and tests.  Known keys:
- *   "attn_variant"      0 = the library chooses the kernel (8-wavefront workgroups; 4-wavefront ones, two to a
+ *   "attn_variant"      0 = the library chooses the workgroup size (8 wavefronts; 4, two workgroups to a
  *                       compute unit, when a full chunk alone gives two workgroups per compute unit), 1 / 2 =
- *                       shared-tile kernel with 4- / 8-wavefront workgroups;
- *   "split_keys"        1 (default) = a launch whose row tiles would occupy at most two thirds of the
- *                       device's compute units hands the last third of long key ranges to extra
- *                       workgroups (the two parts of a tile meet in scratch memory the handle owns:
- *                       launches on one handle must therefore not overlap in time), 0 = never;
- *   "split_min_stages"  the shortest key range (in stages of 128 keys, 64 for variant 1) that is split
- *                       (default 8, at least 2);
- *   "split_bias_stages" stages left out when the handed-over share of a key range is measured: the extra
- *                       work of a helper workgroup, in stages (default 5, not negative);
- *   "split_share_q8"    the share of the remaining stages that is handed over, in 1/256 (default 85: a third);
+ *                       4- / 8-wavefront workgroups;
+ *   "split_keys"        1 (default) = a launch with fewer than two row tiles per compute unit lays the stages
+ *                       (64 or 128 keys each) of all row tiles of a head group end to end and gives every
+ *                       workgroup of the group an equal range of them; tiles shared by several workgroups are
+ *                       finished from partial results in the handle's scratch memory; 0 = always one
+ *                       workgroup per row tile;
+ *   "stream_wgs"        workgroups per head group of such a launch (default 0: as many as the device has
+ *                       compute units for); a value of 1..255 also forces this mode for launches of any size
+ *                       with at most 64 segments;
  *   "decode_parts"      workgroups that share the keys of one (request, kv head) in tetri_decode_attn
  *                       (default 0: chosen from num_reqs and max_ctx_len);
  *   "transfer_slabs"    (K / V, head) slabs one workgroup of tetri_kv_export / tetri_kv_import moves

@@ -75,8 +75,17 @@ __device__ __forceinline__ float half_swap_sum(float x)
 // compiler does not see this as a memory access, so it inserts no waits for it: the caller
 // orders it with wait_vm<N>() below.  (The compiler's own tracking of such loads cannot tell
 // apart two buffers that are slices of one array and falls back to waiting for everything.)
+// Wave-uniform operands of the loads below, marked as such: they go into scalar registers whatever
+// the compiler thinks of where they were computed.
+__device__ __forceinline__ const void *uniform_ptr(const void *p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const void *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
 {
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 // A group of such loads that share one scalar base and one LDS base: instruction i moves
@@ -85,6 +94,8 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
 // once per group.
 __device__ __forceinline__ void dma16_group4(const void *sbase, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, uint32_t lds_base)
 {
+    sbase = uniform_ptr(sbase);
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, %4\n\t"
                  "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
@@ -93,6 +104,8 @@ __device__ __forceinline__ void dma16_group4(const void *sbase, uint32_t v0, uin
 }
 __device__ __forceinline__ void dma16_group2(const void *sbase, uint32_t v0, uint32_t v1, uint32_t lds_base)
 {
+    sbase = uniform_ptr(sbase);
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, %2\n\t"
                  "global_load_lds_dwordx4 %1, %2 offset:1024" ::"v"(v0), "v"(v1), "s"(sbase), "s"(lds_base) : "memory", "m0");
@@ -114,6 +127,7 @@ __device__ __forceinline__ void coherent_stores_done() { asm volatile("s_waitcnt
 // of LDS at lds_dst; it is there after wait_vm<0>().
 __device__ __forceinline__ void peek_coherent(const void *p, uint32_t lds_dst)
 {
+    lds_dst = __builtin_amdgcn_readfirstlane(lds_dst);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off sc1" ::"v"(p), "s"(lds_dst) : "memory", "m0");
 }
 // A partial result read back in one go: n 16-byte vectors 1 KB apart from `po` on, two floats 128
@@ -173,10 +187,17 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
 // compiler barrier for memory accesses, so LDS reads stay behind it.
 template <int N> __device__ __forceinline__ void wait_vm()
 {
-    static_assert(N == 0 || N == 4 || N == 8, "unsupported count");
-    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    static_assert(N >= 0 && N < 64, "the counter has six bits");
+    // s_waitcnt operand of gfx9: vmcnt in bits 3:0 and 15:14, expcnt (6:4) and lgkmcnt (11:8) left at their maxima
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+    asm volatile("" ::: "memory");
+}
+// A workgroup barrier that orders LDS accesses only: vector-memory operations in flight (loads into
+// other LDS buffers, stores of results) are not waited for.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // Everything a wavefront needs to know about where its workgroup's keys come from.

@@ -29,11 +29,20 @@
 //   * LDS rows are XOR-swizzled in 16-byte units (the permutation is applied to the per-lane
 //     global address of the direct load) so that the 128-bit K reads and the transposing V reads
 //     are bank-conflict free.
-//   * Workgroup ids are remapped so that all row tiles of a kv head run on one XCD (one L2).
-//   * A launch with fewer row tiles than two thirds of the CUs adds helper workgroups: a tile
-//     with a long key range hands its last stages to a helper (two tiles per helper) and the two
-//     partial results meet in scratch memory of the library's handle, without anybody waiting
-//     (tile_job, merge_pieces_and_store).
+//   * Workgroup ids are remapped so that all workgroups of a kv head run on one XCD (one L2).
+//   * Two ways of handing out the work of a head group (all row tiles of the heads of one
+//     workgroup column):
+//       - tile mode: one workgroup per row tile, long (late) tiles first; for launches with at
+//         least two workgroups per compute unit;
+//       - stream mode: the stages of all tiles of the head group, laid end to end in tile order,
+//         are cut into G equal ranges, one per workgroup (G = compute units / head groups), so
+//         every compute unit gets the same number of stages however the causal triangle and the
+//         segment lengths fall.  A range may start and end inside a tile: the pieces of such a
+//         tile meet in scratch memory of the library's handle, without anybody waiting: every
+//         piece but the last to arrive leaves its unnormalised (O, m, row sum) there, the last
+//         one merges all of them in piece order (see finish_tile).  A workgroup whose range
+//         spans several tiles runs them as consecutive jobs; the first K/V stage and the Q rows of
+//         the next job are requested before the current job's epilogue.
 //   * The fused form of the launch has further workgroups that copy the chunk's new K/V rows
 //     into the page pool (append_rows).
 #include "attn_common.h"
@@ -79,14 +88,34 @@ template <int D> __host__ __device__ __forceinline__ constexpr uint32_t v_inst_x
     return (uint32_t)(v_swizzle<D>((64 / (D / 8)) * i) * 16);
 }
 
-// Wave-uniform pieces of a wavefront's load addresses, fixed for the whole kernel.
+// Where the keys of one job (a stage range of one row tile) come from; wave-uniform.
+struct JobSrc {
+    int bt_off;                 // block-table row of the tile's segment: entries from the start of the table
+    uint32_t new_off;           // first row of the segment, kv head of the workgroup: bytes from the start of k_new / v_new
+    int L;                      // cached tokens of the segment's request
+    int n_new;                  // new keys any row of the tile may see
+    int n_ctx_tiles;            // stages of cached keys
+};
+
+// One job of a workgroup: stages [it_begin, it_end) of one row tile; wave-uniform.
+struct Job {
+    int seg_cu, n_s, t0;        // the tile's segment starts at chunk row seg_cu and has n_s rows; the tile starts at its row t0
+    int tile_index;             // index of the tile in the chunk (names its arrival counters)
+    int it_begin, it_end;
+    int piece, npieces, wf;     // which of the tile's pieces this is, how many there are, the workgroup of piece 0
+    JobSrc src;
+};
+
+// Wave-uniform pieces of a wavefront's load addresses that no job changes.
 struct WaveSrc {
-    const char *pool_k;         // K block of kv head kh in page 0 of the pool
+    const int32_t *bt;          // the block table
+    const char *new_k, *new_v;  // k_new and v_new
+    const char *pool_k;         // K block of the workgroup's kv head in page 0 of the pool
     uint32_t page_bytes;        // one page: K and V blocks of every kv head
     uint32_t v_delta;           // from a page's K block to its V block of the same head
-    const char *new_k, *new_v;  // first row of the segment, kv head kh, in k_new / v_new
     uint32_t stage_new_bytes;   // a stage's worth of rows in k_new / v_new
     uint32_t wave_new_bytes;    // a wavefront's 16 rows
+    int max_blocks;
 };
 
 // The direct-to-LDS loads of this wavefront's 16 rows of one stage (K and V): one scalar base per
@@ -96,32 +125,31 @@ struct StageLoads {
     uint32_t step;              // bytes the rows of two instructions are further apart than 1 KB
     uint32_t kdst;              // LDS byte address of the K rows; the V rows are 2 * STAGE_BYTES further
     int j0, limit;              // first key row, and the end of the key range it belongs to
-    bool ctx;                   // pool rows (else rows of k_new / v_new)
     uint32_t ko, vo;            // per-lane byte offsets of the first instruction's rows, K and V
 };
 
-// Where stage `it` comes from.  Returns whether all 16 rows exist.
+// Where stage `it` of a job comes from.  Returns whether all 16 rows exist.
 template <int D, int KS>
-__device__ __forceinline__ bool describe_stage_loads(const KeySource &ks, const WaveSrc &ws, const LaneOffsets<D> &lo, int page, int it,
+__device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const WaveSrc &ws, const LaneOffsets<D> &lo, int page, int it,
                                                      int wave, int new_row_bytes, uint32_t k_lds, StageLoads &sl)
 {
     constexpr int RPI = 64 / (D / 8);
     constexpr int STAGE = kBNW * KS;
-    sl.ctx = it < ks.n_ctx_tiles;
-    const int jn = it - ks.n_ctx_tiles;
-    sl.j0 = (sl.ctx ? it : jn) * STAGE + 16 * wave;
-    sl.limit = sl.ctx ? ks.L : ks.n_new;
+    const bool ctx = it < src.n_ctx_tiles;
+    const int jn = it - src.n_ctx_tiles;
+    sl.j0 = (ctx ? it : jn) * STAGE + 16 * wave;
+    sl.limit = ctx ? src.L : src.n_new;
     sl.kdst = k_lds + wave * (16 * D * 2);
-    sl.ko = sl.ctx ? lo.k_ctx : lo.k_new;
-    sl.vo = sl.ctx ? lo.v_ctx : lo.v_new;
+    sl.ko = ctx ? lo.k_ctx : lo.k_new;
+    sl.vo = ctx ? lo.v_ctx : lo.v_new;
     // pool rows of an instruction follow the previous one's directly (the immediate offset covers
     // it); rows of k_new / v_new are `step` bytes further apart than that
-    if (sl.ctx) {
+    if (ctx) {
         sl.kb = ws.pool_k + (size_t)page * ws.page_bytes;
         sl.vb = sl.kb + ws.v_delta;
         sl.step = 0;
     } else {
-        const size_t off = (size_t)jn * ws.stage_new_bytes + (size_t)wave * ws.wave_new_bytes;
+        const size_t off = (size_t)src.new_off + (size_t)jn * ws.stage_new_bytes + (size_t)wave * ws.wave_new_bytes;
         sl.kb = ws.new_k + off;
         sl.vb = ws.new_v + off;
         sl.step = RPI * new_row_bytes - 1024;
@@ -159,11 +187,25 @@ __device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool ful
     }
 }
 
+// Physical page of the 16 cached rows wavefront `wave` loads in stage `it` (unused for stages of
+// new keys).  Read through the constant address space: a scalar load, off the vector-memory queue.
 template <int KS>
-__device__ __forceinline__ int load_stage_page(const KeySource &ks, int it, int wave)
+__device__ __forceinline__ int load_stage_page(const int32_t *bt_row, int max_blocks, int it, int wave)
 {
-    const const_i32 *bt = (const const_i32 *)(uintptr_t)ks.bt_row;
-    return bt[min(it * (kBNW * KS / kPage) + wave, ks.max_blocks - 1)];   // clamped entries are never used
+    const const_i32 *bt = (const const_i32 *)(uintptr_t)bt_row;
+    return bt[min(it * (kBNW * KS / kPage) + wave, max_blocks - 1)];   // clamped entries are never used
+}
+
+// Stages of new keys of the m row tiles before tile m of a segment: the sum over i = 1..m of
+// ceil(i * BM / STAGE), BM = 1 << bm_shift rows per tile.
+template <int STAGE>
+__device__ __forceinline__ int new_stages_before(int m, int bm_shift)
+{
+    constexpr int SS = STAGE == 128 ? 7 : 6;
+    static_assert(STAGE == 128 || STAGE == 64, "stage of 64 or 128 keys");
+    if (bm_shift >= SS) return ((m * (m + 1)) >> 1) << (bm_shift - SS);
+    const int rs = SS - bm_shift, q = m >> rs, rem = m & ((1 << rs) - 1);
+    return (((q * (q + 1)) >> 1) << rs) + rem * (q + 1);
 }
 
 // Fused KV append: workgroup `blk` of `nblk` copies chunk rows blk, blk + nblk, ... (K and V of
@@ -211,9 +253,9 @@ __device__ __forceinline__ void append_rows(const AttnParams &p, unsigned long l
 }
 
 // The launch parameters as the jobs of a workgroup read them: from a copy in LDS (the kernel
-// argument segment is host memory, one read of it per launch is enough), word by word into
-// scalar registers, anew by every job and once more after a job's main loop, so that they do not
-// occupy scalar registers across the loop.
+// argument segment is slow to re-read, one read of it per launch is enough), word by word into
+// scalar registers, anew wherever they are needed, so that they do not occupy scalar registers
+// across the main loop.
 __device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
 {
     static_assert(sizeof(AttnParams) % 4 == 0, "copied as 32-bit words");
@@ -225,66 +267,128 @@ __device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
     return __builtin_bit_cast(AttnParams, w);
 }
 
-// What a helper workgroup's wavefront remembers of its first tile when it goes on to its second
-// one before the hand-over of the first is settled (see tile_job).
+// A piece of a tile whose result is in the scratch memory but whose arrival is not settled yet:
+// what a wavefront remembers of it while it goes on with the workgroup's next job (see tile_job).
 struct Handover {
-    int unit = -1;          // (head group, tile, slot) whose partial result is stored but not announced yet
-    int old = 0;            // lane 0: what the arrival counter held when it was announced
+    int unit = -1;          // arrival counter of the (head group, tile, slot); -1: nothing pending
+    int old = 0;            // lane 0: what the counter held when this piece was announced
     bool announced = false;
+    bool fresh = false;     // the partial result's stores are the wavefront's most recent memory operations
     int seg_cu = 0, t0 = 0, n_s = 0;    // where the tile's rows are
+    int npieces = 0, wf = 0;
 };
 
-// The two pieces of a split tile, merged, normalised and written.  (o, m, l): this wavefront's
-// piece; `other`: the other piece in the scratch memory.  Whichever piece calls this, the value is
-// fma(piece 1, its weight, piece 0 * its weight).
+// Byte size of one wavefront's partial result in the scratch memory: O (32 rows x D floats in the
+// accumulator layout: 16-byte vector (db * 4 + q4) of lane l at index (db * 4 + q4) * 64 + l),
+// then m and the row sum of the 32 rows.
+// Store instructions a wavefront issues for one partial result (16-byte vectors of O, then m and the row sum).
+template <int D> constexpr int kPartialStores = (D / 32) * 4 + 2;
+
+template <int D> constexpr size_t unit_bytes() { return (size_t)(D / 32) * 4 * 64 * 16 + 2 * 32 * 4; }
+
+// Where piece i of a tile keeps its partial result: a workgroup has two places, one for a piece
+// that is not the first of its tile (only a workgroup's first job can be one) and one for a first
+// piece (only its last job can be an unfinished one).
 template <int D>
-__device__ __forceinline__ void merge_pieces_and_store(f32x16 (&o)[D / 32], float m, float l, const char *other, int piece, int lane,
-                                                       bool row_ok, uint16_t *orow)
+__device__ __forceinline__ char *piece_scratch(const AttnParams &p, int grp, int wf, int i, int slot)
+{
+    const size_t unit = (((size_t)grp * p.stream_wgs + wf + i) * 2 + (i == 0 ? 1 : 0)) * kSlots + slot;
+    return p.scratch + unit * unit_bytes<D>();
+}
+
+// All pieces of a tile are there: merge them, normalise, write the rows.  `mine` is the piece this
+// wavefront still holds in registers (o, m, l), or -1 when all of them are read from the scratch
+// memory.  Whoever calls this, the value is the same: the pieces are combined one after the other
+// in piece order, each step bringing the running result and the next piece to their common
+// reference exponent: acc = acc * 2^(m_acc - m') + O_i * 2^(m_i - m'), m' = max(m_acc, m_i).
+// One pass over the scratch memory: a piece's O, m and row sum arrive in one round trip.
+template <int D>
+__device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf, int npieces, int mine, int slot, f32x16 (&o)[D / 32], float m,
+                                            float l, int lane, bool row_ok, uint16_t *orow)
 {
     constexpr int DBLK = D / 32;
+    constexpr size_t STATS = (size_t)DBLK * 4 * 64 * 16;
     const int half = lane >> 5, l32 = lane & 31;
-    const f32x4 *qo = reinterpret_cast<const f32x4 *>(other);
-    const float *qs = reinterpret_cast<const float *>(other + (size_t)DBLK * 4 * 64 * 16);
-    float m1, l1;
-    f32x4 x[DBLK * 4];
-    load_partial(qo + lane, qs + l32, x, m1, l1);
-    const float mstar = fmaxf(m, m1);
-    const float w_own = __builtin_amdgcn_exp2f(m - mstar), w_oth = __builtin_amdgcn_exp2f(m1 - mstar);
-    l = piece == 0 ? __builtin_fmaf(l1, w_oth, l * w_own) : __builtin_fmaf(l, w_own, l1 * w_oth);
+    float macc = 0.f, lacc = 0.f;
+    f32x16 acc[DBLK];
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+    for (int i = 0; i < npieces; ++i) {
+        float mi, li;
+        f32x4 x[DBLK * 4];
+        if (i == mine) {
+            mi = m; li = l;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[db * 4 + v / 4][v % 4] = o[db][v];
+        } else {
+            const char *src = piece_scratch<D>(p, grp, wf, i, slot);
+            load_partial(reinterpret_cast<const f32x4 *>(src) + lane, reinterpret_cast<const float *>(src + STATS) + l32, x, mi, li);
+        }
+        if (i == 0) {
+            macc = mi; lacc = li;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[db][v] = x[db * 4 + v / 4][v % 4];
+        } else {
+            const float mnew = fmaxf(macc, mi);
+            const float wa = __builtin_amdgcn_exp2f(macc - mnew), wi = __builtin_amdgcn_exp2f(mi - mnew);
+            macc = mnew;
+            lacc = __builtin_fmaf(li, wi, lacc * wa);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[db][v] = __builtin_fmaf(x[db * 4 + v / 4][v % 4], wi, acc[db][v] * wa);
+        }
+    }
     if (!row_ok) return;
-    const float inv = __builtin_amdgcn_rcpf(l);
+    const float inv = __builtin_amdgcn_rcpf(lacc);
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             bf16x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
-                const float r = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
-                w[e] = (__bf16)(r * inv);
-            }
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[db][q4 * 4 + e] * inv);
             *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
         }
 }
 
-// One piece of one row tile of one head group: `piece` 0 is the whole key range, or, when the
-// launch splits key ranges (p.tail_q8 != 0), all but its last third; piece 1 is that last third.
-// The two pieces of a split tile meet through the launch's scratch memory: each wavefront stores
-// its unnormalised (O, m, row sum), and the one that finds the other's already there merges and
-// writes the output rows.  Nobody waits for anybody.
+// What carries over from one job of a workgroup to the next.
+template <int D>
+struct Carry {
+    bf16x8 qf[D / 16];      // Q fragments of the job about to run (requested before the previous job's epilogue)
+    int par;                // stage `it` of the job about to run uses stage buffer (it & 1) ^ par
+    int page;               // page of this wavefront's rows of the stage after the job's first one
+};
+
+// Q fragments (B operand of S^T = K Q^T) of a job: lane holds q[t][16*st + 8*half .. +7].  Lanes
+// past the segment's last row read its first row instead: their results are never stored.
+template <int D>
+__device__ __forceinline__ void request_q(const AttnParams &p, const Job &J, int head, int rbk, int lane, bf16x8 (&qf)[D / 16])
+{
+    const int t = J.t0 + 32 * rbk + (lane & 31);
+    const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(J.seg_cu + (t < J.n_s ? t : 0)) * p.Hq + head) * D);
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) qf[st] = __builtin_bit_cast(bf16x8, qp[2 * st + (lane >> 5)]);
+}
+
+// One job: stages [J.it_begin, J.it_end) of one row tile of one head group.  When the stage range is
+// the whole key range of the tile (J.npieces == 1) the rows are finished here; otherwise the pieces
+// of the tile meet through the launch's scratch memory: each wavefront stores its unnormalised
+// (O, m, row sum) and announces it on the tile's arrival counter; the one whose announcement finds
+// all other pieces there merges them and writes the output rows.  Nobody waits for anybody.
+// `next`: the workgroup has a job after this one, N.  On entry the loads of the job's first
+// stage are in flight and cy holds its Q fragments; on exit the same holds for `next`.
 template <int D, int KS>
 __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_job, const AttnParams *params, uint4 *smem, float (*Mstat)[2][32],
-                                         uint32_t (*peek)[64], int grp, int tile_index, int piece, Handover &ho, bool may_defer)
+                                         uint32_t (*peek)[64], int grp, const Job &J, bool next, const Job &N, const WaveSrc &ws, Carry<D> &cy,
+                                         Handover &ho)
 {
-    // a workgroup's first job starts from the kernel arguments themselves: the copy in LDS is only
-    // known to be complete after the job's first barrier
-    AttnParams p = kernarg;
-    if (!first_job) {
-        asm volatile("" ::: "memory");               // keeps this a branch: the reads are not done speculatively
-        p = read_params(params);
-    }
-
     constexpr int CH = D / 8;        // 16-byte chunks per K/V row
     constexpr int KSTEPS = D / 16;   // MFMA steps over d for S^T
     constexpr int DBLK = D / 32;     // 32-row blocks of O^T
@@ -292,6 +396,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     constexpr int STAGE = kBNW * KS; // keys per stage
     constexpr int STAGE_U4 = STAGE * CH;
 
+    // a workgroup's first job starts from the kernel arguments themselves: the copy in LDS is only
+    // known to be complete after the job's first barrier
+    AttnParams p = kernarg;
+    if (!first_job) {
+        asm volatile("" ::: "memory");               // keeps this a branch: the reads are not done speculatively
+        p = read_params(params);
+    }
     // The thread id is made opaque per job: values derived from it are then computed where a job
     // needs them instead of being kept in registers across the whole job loop.
     int tid = threadIdx.x;
@@ -300,76 +411,15 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = wave % kSlots, kq = wave / kSlots;    // row/head slot, key part
     const int half = lane >> 5, l32 = lane & 31;
-    const int BM = 32 << p.rb_shift;
-    const int S = p.S;
-    int tile = tile_index;
-
-    // ---- which (segment, row tile) is it?  Tiles never span two segments.  64 segments are
-    // examined at a time: lane l takes segment s0 + l, a wave-wide prefix sum of the tile counts
-    // finds the segment that owns `tile`.  The lane also fetches what the owner will need next
-    // (context length, the page of this wavefront's first rows), so that the kernel's first loads
-    // of K and V are one memory round trip away from its start, not three.
-    int s = -1, t0 = -1, seg_cu = 0, n_s = 0, L = 0, page = 0, page_hi = 0;
-    const int first_page = min(wave, p.max_blocks - 1), first_page_hi = min(wave + kSlots, p.max_blocks - 1);
-    for (int s0 = 0; s0 < S; s0 += 64) {
-        const int idx = s0 + lane;
-        const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
-        const int ctx_len = idx < S ? p.ctx[idx] : 0;
-        const int pg = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page] : 0;
-        const int pg_hi = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page_hi] : 0;
-        const int nt = (b - a + BM - 1) >> (5 + p.rb_shift);   // 0 for lanes past the last segment
-        int incl = nt;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
-        const unsigned long long owner = __builtin_amdgcn_ballot_w64(tile >= incl - nt && tile < incl);
-        if (owner != 0) {
-            const int src = __builtin_ctzll(owner);
-            s = s0 + src;
-            t0 = (tile - __builtin_amdgcn_readlane(incl - nt, src)) * BM;
-            seg_cu = __builtin_amdgcn_readlane(a, src);
-            n_s = __builtin_amdgcn_readlane(b - a, src);
-            L = __builtin_amdgcn_readlane(ctx_len, src);
-            page = __builtin_amdgcn_readlane(pg, src);
-            page_hi = __builtin_amdgcn_readlane(pg_hi, src);
-            break;
-        }
-        tile -= __builtin_amdgcn_readlane(incl, 63);
-    }
     const int hh = slot & (p.hpw - 1), rbk = slot >> p.hpw_shift;
     const int head = grp * p.hpw + hh;
-    if (t0 < 0) {
-        // padding rows [cu[S], C): written as +0
-        const int r0 = p.cu[S] + tile * BM + 32 * rbk;
-        if (r0 >= p.C || kq != 0 || piece != 0) return;
-        const int r = r0 + l32;
-        if (r < p.C) {
-            uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + head) * D);
-            for (int c = half; c < CH; c += 2) o[c] = make_uint4(0, 0, 0, 0);
-        }
-        return;
-    }
-    TETRI_MARK(1);
-    KeySource ks;
-    ks.pages = p.pages; ks.k_new = p.k_new; ks.v_new = p.v_new;
-    ks.bt_row = p.bt + (size_t)s * p.max_blocks;
-    ks.Hkv = p.Hkv; ks.kh = magic_div(grp, p.kv_magic); ks.row_base = seg_cu; ks.L = L;
-    ks.n_new = min(n_s, t0 + BM);                      // new keys any row of this tile may see
-    ks.n_ctx_tiles = (L + STAGE - 1) / STAGE;
-    ks.max_blocks = p.max_blocks;
-    const int n_all = ks.n_ctx_tiles + (ks.n_new + STAGE - 1) / STAGE;
-    // 0 when the launch does not split, and for key ranges too short to be worth a hand-over.  A
-    // helper has about split_bias stages' worth of extra work (a second tile's prologue, handing
-    // its first result over): the three workgroups of two tiles finish together when each tile
-    // hands over a third of what exceeds that.
-    const int n_tail = n_all >= p.split_min ? (max(n_all - p.split_bias, 0) * p.tail_q8 + 128) >> 8 : 0;
-    if (piece != 0 && n_tail == 0) return;
-    const int it_begin = piece == 0 ? 0 : n_all - n_tail;
-    const int n_stages = piece == 0 ? n_all - n_tail : n_all;          // end of this piece's stage range
+    const JobSrc src = J.src, nsrc = N.src;           // by value: selecting between fields of two referenced jobs would keep them in memory
+    const int n_it_begin = N.it_begin;
+    const int L = src.L, n_s = J.n_s;
+    const int it_begin = J.it_begin, n_stages = J.it_end;      // end of this piece's stage range
+    const int par = __builtin_amdgcn_readfirstlane(cy.par);
 
-    const int tw0 = t0 + 32 * rbk;         // first local row of this wavefront
+    const int tw0 = J.t0 + 32 * rbk;       // first local row of this wavefront
     const int t = tw0 + l32;               // local row of this lane's query
     const bool row_ok = t < n_s;
     const bool wave_has_rows = tw0 < n_s;
@@ -380,50 +430,21 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     const uint32_t smem_lds = lds_address(smem);
     constexpr uint32_t STAGE_BYTES = STAGE_U4 * 16;   // bytes of one matrix of one stage
 
-    WaveSrc ws;
-    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)ks.kh * (kPage * D * 2);
-    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
-    ws.v_delta = p.Hkv * (kPage * D * 2);
-    {
-        const size_t off = ((size_t)ks.row_base * p.Hkv + ks.kh) * (size_t)(D * 2);
-        ws.new_k = reinterpret_cast<const char *>(p.k_new) + off;
-        ws.new_v = reinterpret_cast<const char *>(p.v_new) + off;
-    }
-    ws.stage_new_bytes = STAGE * new_row_bytes;
-    ws.wave_new_bytes = 16 * new_row_bytes;
-    static_assert(kBNW * KS / kPage == kSlots * KS, "stage 0: wavefront w loads page w of the segment");
-    // Stage 0: the wavefronts of key part 0 reach this point first (the older wavefront of a SIMD
-    // is served first), so they issue the loads of their partner in part 1 as well.
-    StageLoads sl;
-    if (kq == 0) {
-        if (it_begin != 0) {                         // the lookup fetched the pages of stage 0
-            page = load_stage_page<KS>(ks, it_begin, wave);
-            page_hi = load_stage_page<KS>(ks, it_begin, wave + kSlots);
-        }
-#pragma unroll
-        for (int part = 0; part < KS; ++part) {
-            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, part == 0 ? page : page_hi, it_begin, wave + part * kSlots, new_row_bytes,
-                                                          smem_lds + (it_begin & 1) * STAGE_BYTES, sl);
-            issue_stage_loads<D, KS>(sl, full, lane);
-        }
-    }
     // The loads of the next stage are not issued by all wavefronts at once right after the barrier:
     // the load unit takes a wavefront's 8 KB in about 128 cycles and a wavefront that finds it busy
     // stalls in front of its own matrix instructions.  Each wavefront has one of four points in
     // the instruction stream between two barriers at which it issues its loads (the two wavefronts
     // of a SIMD use different ones), so that at any time most wavefronts are computing.
+    StageLoads sl;
     bool pend = false;                               // the next stage's loads are described in sl, not issued
     const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
-    page = load_stage_page<KS>(ks, it_begin + 1, wave);
+    int page = __builtin_amdgcn_readfirstlane(cy.page);
+    // a job of one stage: the stage after its first one is the next job's first
+    if (it_begin + 1 >= n_stages && next) page = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin, wave);
 
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[t][16*st + 8*half .. +7].  Lanes
-    // past the segment's last row read its first row instead: their results are never stored.
     bf16x8 qf[KSTEPS];
-    {
-        const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(seg_cu + (row_ok ? t : 0)) * p.Hq + head) * D);
 #pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) qf[st] = __builtin_bit_cast(bf16x8, qp[2 * st + half]);
-    }
+    for (int st = 0; st < KSTEPS; ++st) qf[st] = cy.qf[st];
 
     f32x16 o[DBLK];
 #pragma unroll
@@ -442,34 +463,37 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // (A operand of S^T).  V: for step j (16 keys) and d block db the lane gets keys 16j + 4*half +
     // {0..3, 8..11} of d = 32*db + l32 through two transposing reads (A operand of O^T).
     // The per-lane parts of the addresses (row inside the wavefront's 64-key part, swizzled chunk)
-    // never change: they are computed once; stage buffer and block are added as one byte offset,
-    // which is an instruction immediate wherever it is known at compile time.
+    // never change: the address of step 0 (K) and of d block 0 (V) is computed once and kept; the
+    // swizzles are XORs of chunk bits that the step / block index leaves alone, so step st is that
+    // address ^ (st << 5) and block db that address ^ (db << 6), one operation at the point of use
+    // instead of a register each for the whole loop.  Stage buffer and block are added as one byte
+    // offset, which is an instruction immediate wherever it is known at compile time.
     constexpr int BLOCK_BYTES = 32 * D * 2;            // one 32-key block of K or of V
-    uint32_t kbase[KSTEPS], vbase[DBLK];
+    uint32_t kbase0, vbase0;
     {
         const int r = kq * kBNW + l32;
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) kbase[st] = r * D * 2 + (((2 * st + half) ^ k_swizzle<D>(r)) << 4);
+        kbase0 = r * D * 2 + ((half ^ k_swizzle<D>(r)) << 4);
         const int rv = kq * kBNW + 4 * half + (i16 >> 2);
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db) {
-            const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
-            vbase[db] = 2 * STAGE_BYTES + rv * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
-        }
+        const int d0 = 16 * (blk & 1) + 4 * (i16 & 3);
+        vbase0 = 2 * STAGE_BYTES + rv * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
     }
     const char *smem_b = reinterpret_cast<const char *>(smem);
+    // byte offset of the stage buffer that holds stage `it` of this job
+    auto buf_of = [&](int it) -> int { return ((it & 1) ^ par) * (int)STAGE_BYTES; };
     // off = buffer * STAGE_BYTES + block * BLOCK_BYTES
     auto load_k = [&](bf16x8 (&kf)[KSTEPS], int off) {
+        asm volatile("" : "+v"(kbase0));               // the XORs below stay here: hoisted out of the loop they would be registers again
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st)
-            kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + kbase[st] + off));
+            kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + (kbase0 ^ (st << 5)) + off));
     };
     auto load_v = [&](s16x8 (&vf)[2 * DBLK], int off) {
+        asm volatile("" : "+v"(vbase0));
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int db = 0; db < DBLK; ++db) {
-                const char *a = smem_b + vbase[db] + off + j * (16 * D * 2);
+                const char *a = smem_b + (vbase0 ^ (db << 6)) + off + j * (16 * D * 2);
                 const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
                 const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * D * 2));
                 vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -480,19 +504,19 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // those inside the key range and not entirely past the wavefront's rows.
     auto stage_blocks = [&](int it) -> int {
         if (!wave_has_rows) return 0;
-        const bool is_ctx = it < ks.n_ctx_tiles;
-        const int part0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW;
+        const bool is_ctx = it < src.n_ctx_tiles;
+        const int part0 = (is_ctx ? it : it - src.n_ctx_tiles) * STAGE + kq * kBNW;
         int nblk = 0;
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
             const int key0 = part0 + kb * 32;
-            if (is_ctx ? key0 < L : (key0 < ks.n_new && key0 <= tw0 + 31)) nblk = kb + 1;
+            if (is_ctx ? key0 < L : (key0 < src.n_new && key0 <= tw0 + 31)) nblk = kb + 1;
         }
         return nblk;
     };
     // Make stage `it` the current one: its loads have landed for every wavefront, nobody reads the
-    // other buffer any more, so the loads of stage it+1 can go there.  `page` always belongs to
-    // the stage whose loads are issued next; it is fetched one stage ahead.
+    // other buffer any more, so the loads of the stage after it can go there.  `page` always belongs
+    // to the stage whose loads are issued next; it is fetched one stage ahead.
     // Entering a stage has two halves: the wait, after which the wavefront may read the stage (it
     // requests its first K fragments from LDS right away), and handing out the next stage's loads.
     // `pv_before`: a PV product is pending, i.e. deferred loads will meet their issue point before
@@ -512,13 +536,28 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         __syncthreads();
         return stage_blocks(it);
     };
+    // The loads of the stage after `it`: the job's next stage, or after its last stage the first
+    // stage of the workgroup's next job, into the buffer stage `it` does not use.
     auto next_stage_loads = [&](int it, int nb, bool pv_before) {
-        if (it + 1 < n_stages) {
-            const bool full = describe_stage_loads<D, KS>(ks, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + ((it + 1) & 1) * STAGE_BYTES, sl);
+        const bool in_job = it + 1 < n_stages;
+        if (in_job || next) {
+            JobSrc from;                                 // field by field: a choice between two addresses would keep both jobs in memory
+            from.bt_off = in_job ? src.bt_off : nsrc.bt_off;
+            from.new_off = in_job ? src.new_off : nsrc.new_off;
+            from.L = in_job ? src.L : nsrc.L;
+            from.n_new = in_job ? src.n_new : nsrc.n_new;
+            from.n_ctx_tiles = in_job ? src.n_ctx_tiles : nsrc.n_ctx_tiles;
+            const int nit = in_job ? it + 1 : n_it_begin;
+            const bool full = describe_stage_loads<D, KS>(from, ws, lo, page, nit, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
             if (full && pv_before && nb != 0 && load_point != 0) pend = true;
             else issue_stage_loads<D, KS>(sl, full, lane);
+            // the page of the stage after that one (past the end of the next job: never used)
+            if (in_job && it + 2 >= n_stages) {
+                if (next) page = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin, wave);
+            } else {
+                page = load_stage_page<KS>(ws.bt + from.bt_off, ws.max_blocks, nit + 1, wave);
+            }
         }
-        page = load_stage_page<KS>(ks, it + 2, wave);
     };
     auto qk = [&](const bf16x8 (&kf)[KSTEPS]) -> f32x16 {
         f32x16 sacc;
@@ -535,24 +574,42 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // Every wavefront enters every stage exactly once (one barrier each), whether or not it has
     // blocks there.
     int it = it_begin;
-    TETRI_MARK(2);
-    int nblk = sync_stage(it);
-    if (ho.unit >= 0 && !ho.announced) {
-        // the previous tile's partial result was stored before this job began; the wait in front of
-        // the barrier just passed covered those stores, so it can be announced now.  What the
-        // counter held is looked at when this job is done.
-        if (lane == 0) ho.old = atomicAdd(p.counters + ho.unit, 1);
-        ho.announced = true;
+    TETRI_MARK((first_job ? 0 : 12) + 2);
+    int nblk;
+    // A partial result left by an earlier job is announced behind a wait for all of this wavefront's memory
+    // operations, its stores included.  What the counter held is looked at when the workgroup's jobs are done.
+    auto announce = [&]() {
+        if (ho.unit >= 0 && !ho.announced) {
+            if (lane == 0) ho.old = atomicAdd(p.counters + ho.unit, 1);
+            ho.announced = true;
+        }
+    };
+    if (ho.unit >= 0 && ho.fresh) {
+        // The job before this one left a partial result: its stores were issued after this job's first stage and
+        // Q rows were requested, they are this wavefront's most recent memory operations, and they go all the way
+        // to memory.  Memory operations complete in the order they were issued: the first stage waits for all but
+        // those stores; the announcement follows at the job's second stage (a job of one stage: at the next job's
+        // first stage, or when the workgroup's jobs are done).
+        wait_vm<kPartialStores<D>>();
+        __builtin_amdgcn_s_barrier();
+        nblk = stage_blocks(it);
+        ho.fresh = false;
+    } else {
+        nblk = sync_stage(it);
+        announce();
     }
-    TETRI_MARK(3);
+    TETRI_MARK((first_job ? 0 : 12) + 3);
     while (nblk == 0 && it + 1 < n_stages) {
         next_stage_loads(it, 0, false);
         nblk = sync_stage(++it);
+        announce();
     }
-    if (nblk != 0) {
+    if (nblk == 0) {
+        next_stage_loads(it, 0, false);                // the job's last stage and nothing to do in it: the next job's loads
+    } else {
         int kb = 0;
         bf16x8 kf[KSTEPS];
-        load_k(kf, (it & 1) * STAGE_BYTES);
+        load_k(kf, buf_of(it));
         next_stage_loads(it, nblk, false);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
@@ -648,13 +705,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
         // after the last block.
         auto block = [&](f32x16 &s_cur, f32x16 &s_next) -> bool {
-            const bool is_ctx = it < ks.n_ctx_tiles;
-            const int key0 = (is_ctx ? it : it - ks.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
+            const bool is_ctx = it < src.n_ctx_tiles;
+            const int key0 = (is_ctx ? it : it - src.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
             const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
             const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
             // V fragments of this block: in registers before the stage may be left
             s16x8 vf[2 * DBLK];
-            load_v(vf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
+            load_v(vf, buf_of(it) + kb * BLOCK_BYTES);
             // ---- the block after this one
             bool have_next = true, entered = false;
             if (kb + 1 < nblk) {
@@ -665,11 +722,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 nblk = 0;
                 while (nblk == 0 && it + 1 < n_stages) {
                     nblk = sync_stage(++it);
+                    announce();
                     if (nblk == 0) next_stage_loads(it, 0, true);
                 }
                 have_next = entered = nblk != 0;
             }
-            if (have_next) load_k(kf, (it & 1) * STAGE_BYTES + kb * BLOCK_BYTES);
+            if (have_next) load_k(kf, buf_of(it) + kb * BLOCK_BYTES);
             if (entered) next_stage_loads(it, nblk, true);
             else issue_pending(3);
             // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
@@ -690,22 +748,39 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             if (!block(s_b, s_a)) break;
         }
     }
+    if (pend) {                                      // the next job's loads, if their issue point was not reached
+        issue_stage_loads<D, KS>(sl, true, lane);
+        pend = false;
+    }
 
-    TETRI_MARK(4);
-    // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes.
-    // The partial O goes into the stage buffer that held the stage before the last one: nobody reads
-    // it any more once every wavefront has entered the last stage, so no barrier is needed before
-    // writing.  Its K region takes slots 0 and 1, its V region slots 2 and 3; lane l's four
-    // consecutive accumulator elements are one 16-byte unit.
-    // A split tile: is the other piece there already?  The answer travels while the key parts merge.
+    TETRI_MARK((first_job ? 0 : 12) + 4);
+    // ---- the next job: its Q rows are requested now, so that they arrive during this job's epilogue
     asm volatile("" ::: "memory");                   // a fresh read, not the values from before the loop
     const AttnParams pe = read_params(params);
-    const size_t unit = ((size_t)grp * pe.tiles + tile_index) * kSlots + slot;
-    if (n_tail != 0 && kq == 0 && wave_has_rows) peek_coherent(pe.counters + unit, lds_address(peek[slot]));
+    if (next) {
+        request_q<D>(pe, N, head, rbk, lane, cy.qf);
+        cy.par = ((n_stages & 1) ^ par) ^ (n_it_begin & 1);      // its first stage goes where stage n_stages of this job would
+        cy.page = page;
+    }
+    // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes.
+    // The partial O goes into a stage buffer nobody reads any more.  After a workgroup's last job that
+    // is the buffer of the stage before the last one (every wavefront has entered the last stage, so no
+    // barrier is needed before writing).  With a next job that buffer is receiving the next job's first
+    // stage: then the last stage's own buffer is used, after a barrier that says everybody has left it.
+    // The buffer's K region takes slots 0 and 1, its V region slots 2 and 3; lane l's four consecutive
+    // accumulator elements are one 16-byte unit.
+    const size_t unit = ((size_t)grp * pe.tiles + J.tile_index) * kSlots + slot;
+    const bool pieces = J.npieces > 1;
+    // A tile of several pieces and no job after it: are the other pieces there already?  The answer
+    // travels while the key parts merge.
+    if (pieces && !next && kq == 0 && wave_has_rows) peek_coherent(pe.counters + unit, lds_address(peek[slot]));
     float ltot = half_swap_sum(lsum);
     if constexpr (KS == 2) {
         static_assert(2 * (DBLK * 16 * 64 * 4) == STAGE_BYTES, "two slots per matrix region");
-        char *dead = reinterpret_cast<char *>(smem) + (n_stages & 1) * STAGE_BYTES + (slot >> 1) * (2 * STAGE_BYTES);
+        if (next) lds_barrier();
+        TETRI_MARK((first_job ? 0 : 12) + 10);
+        const int dead_off = next ? buf_of(n_stages - 1) : (buf_of(n_stages - 1) ^ (int)STAGE_BYTES);
+        char *dead = reinterpret_cast<char *>(smem) + dead_off + (slot >> 1) * (2 * STAGE_BYTES);
         f32x4 *part = reinterpret_cast<f32x4 *>(dead + (slot & 1) * (DBLK * 16 * 64 * 4));
         if (kq == 1) {
 #pragma unroll
@@ -719,8 +794,8 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 }
             if (half == 0) { Mstat[slot][0][l32] = m; Mstat[slot][1][l32] = ltot; }
         }
-        __syncthreads();
-        TETRI_MARK(5);
+        lds_barrier();
+        TETRI_MARK((first_job ? 0 : 12) + 5);
         if (kq == 1) return;
         const float m1 = Mstat[slot][0][l32], l1 = Mstat[slot][1][l32];
         const float mstar = fmaxf(m, m1);
@@ -740,16 +815,18 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         if (!wave_has_rows) return;
     }
 
-    // ---- a split tile: if the other piece is there, merge with it; else leave (O, m, row sum) in
-    // the scratch memory and announce it, which tells whether the other piece has arrived in the
-    // meantime.  unit = (head group, tile, slot); the counter of a unit goes 0 -> 1 -> 0.
-    if (n_tail != 0) {
-        constexpr size_t UNIT_BYTES = (size_t)DBLK * 4 * 64 * 16 + 2 * 32 * 4;
-        const size_t units = (size_t)pe.groups * pe.tiles * kSlots;
-        char *mine = pe.scratch + ((size_t)piece * units + unit) * UNIT_BYTES;
-        const char *other = pe.scratch + ((size_t)(1 - piece) * units + unit) * UNIT_BYTES;
-        wait_vm<0>();
-        if (__builtin_amdgcn_readfirstlane(peek[slot][lane]) == 0) {
+    TETRI_MARK((first_job ? 0 : 12) + 11);
+    uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t) * pe.Hq + head) * D;
+    // ---- a tile of several pieces.  unit = (head group, tile, slot); its counter starts at 0.
+    if (pieces) {
+        bool all_there = false;
+        if (!next) {
+            wait_vm<0>();
+            all_there = __builtin_amdgcn_readfirstlane(peek[slot][lane]) == J.npieces - 1;
+        }
+        if (!all_there) {
+            // leave (O, m, row sum) in the scratch memory ...
+            char *mine = piece_scratch<D>(pe, grp, J.wf, J.piece, slot);
             f32x4 *po = reinterpret_cast<f32x4 *>(mine);
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
@@ -758,33 +835,42 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     f32x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
+#ifdef TETRI_EXP_NOSTORE
+                    if (!next)
+#endif
                     store_coherent(po + (db * 4 + q4) * 64 + lane, x);
                 }
             float *ps = reinterpret_cast<float *>(mine + (size_t)DBLK * 4 * 64 * 16);
             if (half == 0) { store_coherent(ps + l32, m); store_coherent(ps + 32 + l32, ltot); }
-            if (may_defer) {
-                // a helper with a second tile to do: neither the end of the stores nor the answer of
-                // the arrival counter is waited for here (about 4 us)
+            if (next) {
+                // ... and go on with the next job: neither the end of the stores nor the answer of the
+                // arrival counter is waited for here (about 4 us); the piece is announced after the next
+                // job's first barrier and the answer looked at when the workgroup's jobs are done
                 ho.unit = (int)unit;
                 ho.announced = false;
-                ho.seg_cu = seg_cu; ho.t0 = t0; ho.n_s = n_s;
+                ho.fresh = true;
+                ho.seg_cu = J.seg_cu; ho.t0 = J.t0; ho.n_s = n_s;
+                ho.npieces = J.npieces; ho.wf = J.wf;
+                TETRI_MARK((first_job ? 0 : 12) + 6);
                 return;
             }
             coherent_stores_done();                  // this wavefront's partial is in memory ...
             int arrived = 0;
             if (lane == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
             arrived = __builtin_amdgcn_readfirstlane(arrived);
-            if (arrived == 0) return;                // first of the two: the other piece finishes the tile
+            if (arrived != J.npieces - 1) {          // not the last one: whoever is finishes the tile
+                TETRI_MARK((first_job ? 0 : 12) + 6);
+                return;
+            }
         }
-        if (lane == 0) pe.counters[unit] = 0;        // ready for the next launch
-        merge_pieces_and_store<D>(o, m, ltot, other, piece, lane, row_ok, pe.out + ((size_t)(ks.row_base + t) * pe.Hq + head) * D);
+        finish_tile<D>(pe, grp, J.wf, J.npieces, J.piece, slot, o, m, ltot, lane, row_ok, orow);
+        TETRI_MARK((first_job ? 0 : 12) + 6);
         return;
     }
 
     // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
     if (!row_ok) return;
     const float inv = __builtin_amdgcn_rcpf(ltot);
-    uint16_t *orow = pe.out + ((size_t)(ks.row_base + t) * pe.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -794,96 +880,322 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
             *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
         }
-    TETRI_MARK(6);
+    TETRI_MARK((first_job ? 0 : 12) + 6);
+}
+
+// Everything about one segment a job needs, as wave-uniform values.
+struct SegInfo {
+    int s, seg_cu, n_s, L;
+};
+
+template <int D, int KS>
+__device__ __forceinline__ JobSrc make_src(const AttnParams &p, int kh, const SegInfo &g, int t0)
+{
+    constexpr int STAGE = kBNW * KS;
+    JobSrc src;
+    src.bt_off = g.s * p.max_blocks;
+    src.new_off = (uint32_t)((g.seg_cu * p.Hkv + kh) * (D * 2));
+    src.L = g.L;
+    src.n_new = min(g.n_s, t0 + (32 << p.rb_shift));
+    src.n_ctx_tiles = (g.L + STAGE - 1) / STAGE;
+    return src;
+}
+
+// Padding rows [cu[S], C) of this head group's heads, written as +0: row first, first + stride, ...
+template <int D>
+__device__ __forceinline__ void zero_padding_rows(const AttnParams &p, int grp, int first, int stride, int tid, int nthreads)
+{
+    constexpr int CH = D / 8;
+    const int per_row = p.hpw * CH;                    // 16-byte vectors per row of this head group: a power of two <= 64
+    const int rows_per_pass = nthreads / per_row;
+    const int x = tid % per_row, rr = tid / per_row;
+    for (int r = p.cu[p.S] + first + rr * stride; r < p.C; r += rows_per_pass * stride) {
+        uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + (size_t)grp * p.hpw) * D);
+        o[x] = make_uint4(0, 0, 0, 0);
+    }
 }
 
 template <int D, int KS>
 __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
 {
-    constexpr int STAGE_U4 = kBNW * KS * (D / 8);
+    constexpr int STAGE = kBNW * KS;
+    constexpr int STAGE_U4 = STAGE * (D / 8);
+    constexpr int NT = kSlots * KS * 64;
     __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stage buffers: K0 | K1 | V0 | V1
     __shared__ float Mstat[kSlots][2][32];
-    __shared__ uint32_t peek[kSlots][64];            // where a look at a split tile's arrival counter lands
+    __shared__ uint32_t peek[kSlots][64];            // where a look at a tile's arrival counter lands
+    __shared__ int4 seg_tab[64];                     // stream mode: (first row, rows, cached tokens) of every segment
     __shared__ AttnParams params;
     TETRI_MARK(0);
 
     // ---- fused KV append: append_blocks workgroups copy the chunk's new K/V rows into their page
-    // slots.  They come after the attention workgroups that certainly have work (attn_first of
-    // them) and before those that probably have none, so that they start on the CUs the attention
-    // grid leaves idle instead of waiting for one to finish.
+    // slots.  They come after the attention workgroups, on the compute units those leave idle.
     int abid = blockIdx.x;                           // index in the attention grid
     if (abid >= p.attn_first) {
         if (abid < p.attn_first + p.append_blocks) {
-            append_rows<D>(p, reinterpret_cast<unsigned long long *>(smem), abid - p.attn_first, p.append_blocks, threadIdx.x, kSlots * KS * 64);
+            append_rows<D>(p, reinterpret_cast<unsigned long long *>(smem), abid - p.attn_first, p.append_blocks, threadIdx.x, NT);
             return;
         }
         abid -= p.append_blocks;
     }
-    // ---- workgroup id -> (head group, job).  The workgroups of a head group run on one XCD (they
-    // read the same K and V through its L2); an XCD has gpx groups and starts their workgroups job
-    // by job.  Without key-range splitting the jobs of a group are its row tiles, late (long) ones
-    // first.  With it (helpers != 0): first the tiles but the last one of the host's bound (which
-    // exists only if the chunk has ragged segments), then the helpers, each doing the last third
-    // of the key ranges of two of those tiles.  The bound's last tile gets no workgroups of its own
-    // (they would start when the first compute unit becomes free and, though empty, end after
-    // everybody else: kernel start-up and the look-up take 2-3 us): its two pieces are one more job of
-    // the workgroup of tile 0, whose key range is the shortest, and of the last helper.
+    // ---- workgroup id -> (head group, index inside the group).  The workgroups of a head group run
+    // on one XCD (they read the same K and V through its L2); an XCD has gpx groups and starts their
+    // workgroups index by index.
     const int xcd = abid % kXcd, local = abid / kXcd;
-    const int job = magic_div(local, p.gpx_magic);
-    const int grp = xcd * p.gpx + (local - job * p.gpx);
-    const int T = p.tiles, H = p.helpers;
-    if (grp >= p.groups || job >= (H != 0 ? T + H - 2 : T)) return;
+    const int widx = magic_div(local, p.gpx_magic);
+    const int grp = xcd * p.gpx + (local - widx * p.gpx);
+    const int G = p.stream_wgs;
+    // the arrival counters of the next launch that divides tiles: all zero when this launch ends
+    if (G != 0)
+        for (int i = abid * NT + threadIdx.x; i < p.n_counters; i += p.attn_grid * NT) p.counters_next[i] = 0;
+    if (grp >= p.groups || widx >= (G != 0 ? G : p.tiles)) return;
     if (threadIdx.x == 0) params = p;                // from scalar registers: no memory read to wait for
-    int piece = 0, first = T - 1 - job, count = 1, extra = 0;
-    if (H != 0) {
-        if (job < T - 1) {
-            first = T - 2 - job;
-            extra = first == 0;
-        } else {
-            piece = 1;
-            first = T - 2 - 2 * (job - (T - 1));
-            count = min(2, first + 1);
-            extra = job == T + H - 3;
+
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slot = wave % kSlots, kq = wave / kSlots;
+    const int bm_shift = 5 + p.rb_shift, BM = 1 << bm_shift;
+    const int S = p.S;
+    const int kh = magic_div(grp, p.kv_magic);
+    const int first_page = min(wave, p.max_blocks - 1), first_page_hi = min(wave + kSlots, p.max_blocks - 1);
+
+    WaveSrc ws;
+    ws.bt = p.bt;
+    ws.new_k = reinterpret_cast<const char *>(p.k_new);
+    ws.new_v = reinterpret_cast<const char *>(p.v_new);
+    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * (kPage * D * 2);
+    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
+    ws.v_delta = p.Hkv * (kPage * D * 2);
+    ws.stage_new_bytes = STAGE * (p.Hkv * D * 2);
+    ws.wave_new_bytes = 16 * (p.Hkv * D * 2);
+    ws.max_blocks = p.max_blocks;
+
+    // ---- the workgroup's first job.  Lane l looks at segment s0 + l (64 at a time); it also fetches
+    // what the owner of the job will need next (context length, the pages of the segment's first
+    // stage), so that the kernel's first loads of K and V are one memory round trip away from its
+    // start wherever possible.
+    Job J;
+    SegInfo seg = {-1, 0, 0, 0};
+    int page = 0, page_hi = 0;
+    // stream mode: the range of stages of this workgroup, [pos, b1) in the group's tile order, of W
+    // stages shared by Gp workgroups; the tile the next job is in: tile j of nt in its segment,
+    // starting at position tile_lin
+    int pos = 0, b1 = 0, W = 1, Gp = 1, j = 0, nt = 1, tile_lin = 0, tile_index = 0;
+    // stream mode, one segment whose block-table row fits two registers per lane: the whole row is fetched together
+    // with the segment lengths, so that the pages of the workgroup's first stage, wherever its range starts, do not
+    // cost a second round trip to memory
+    const bool row_in_lanes = G != 0 && S == 1 && p.max_blocks <= 128;
+    int bt_lo = 0, bt_hi = 0;
+    if (G == 0) {
+        // tile mode: row tile `tile` of the chunk, late (long) tiles first.  Tiles never span two segments.
+        int tile = p.tiles - 1 - widx;
+        tile_index = tile;
+        int t0 = -1;
+        for (int s0 = 0; s0 < S; s0 += 64) {
+            const int idx = s0 + lane;
+            const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
+            const int ctx_len = idx < S ? p.ctx[idx] : 0;
+            const int pg = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page] : 0;
+            const int pg_hi = idx < S ? p.bt[(size_t)idx * p.max_blocks + first_page_hi] : 0;
+            const int ntl = (b - a + BM - 1) >> bm_shift;          // 0 for lanes past the last segment
+            int incl = ntl;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += y;
+            }
+            const unsigned long long owner = __builtin_amdgcn_ballot_w64(tile >= incl - ntl && tile < incl);
+            if (owner != 0) {
+                const int o = __builtin_ctzll(owner);
+                seg.s = s0 + o;
+                t0 = (tile - __builtin_amdgcn_readlane(incl - ntl, o)) * BM;
+                seg.seg_cu = __builtin_amdgcn_readlane(a, o);
+                seg.n_s = __builtin_amdgcn_readlane(b - a, o);
+                seg.L = __builtin_amdgcn_readlane(ctx_len, o);
+                page = __builtin_amdgcn_readlane(pg, o);
+                page_hi = __builtin_amdgcn_readlane(pg_hi, o);
+                break;
+            }
+            tile -= __builtin_amdgcn_readlane(incl, 63);
         }
+        if (t0 < 0) {
+            // past the last segment's tiles: the padding rows [cu[S], C), one 32-row block per wavefront slot
+            if (kq == 0) {
+                const int hh = slot & (p.hpw - 1), rbk = slot >> p.hpw_shift;
+                const int r = p.cu[S] + tile * BM + 32 * rbk + (lane & 31);
+                if (r < p.C) {
+                    uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + grp * p.hpw + hh) * D);
+                    for (int c = lane >> 5; c < D / 8; c += 2) o[c] = make_uint4(0, 0, 0, 0);
+                }
+            }
+            return;
+        }
+        J.seg_cu = seg.seg_cu; J.n_s = seg.n_s; J.t0 = t0; J.tile_index = tile_index;
+        J.src = make_src<D, KS>(p, kh, seg, t0);
+        J.it_begin = 0;
+        J.it_end = J.src.n_ctx_tiles + (J.src.n_new + STAGE - 1) / STAGE;
+        J.piece = 0; J.npieces = 1; J.wf = 0;
+    } else {
+        // stream mode (S <= 64): every workgroup of the group works out the same division
+        const int a = lane < S ? p.cu[lane] : 0, b = lane < S ? p.cu[lane + 1] : 0;
+        const int ctx_len = lane < S ? p.ctx[lane] : 0;
+        const int pg = lane < S ? p.bt[(size_t)lane * p.max_blocks + first_page] : 0;
+        const int pg_hi = lane < S ? p.bt[(size_t)lane * p.max_blocks + first_page_hi] : 0;
+        if (row_in_lanes) {
+            bt_lo = p.bt[min(lane, p.max_blocks - 1)];
+            bt_hi = p.bt[min(lane + 64, p.max_blocks - 1)];
+        }
+        const int n = b - a;
+        const int ntl = (n + BM - 1) >> bm_shift;                  // 0 for lanes past the last segment
+        const int csl = (ctx_len + STAGE - 1) / STAGE;
+        const int wk = ntl > 0 ? ntl * csl + new_stages_before<STAGE>(ntl - 1, bm_shift) + (n + STAGE - 1) / STAGE : 0;
+        if (lane < S) seg_tab[lane] = make_int4(a, n, ctx_len, 0);  // every wavefront writes the same values
+        int t_incl = ntl, w_incl = wk;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(t_incl, d, 64), z = __shfl_up(w_incl, d, 64);
+            if (lane >= d) { t_incl += y; w_incl += z; }
+        }
+        W = __builtin_amdgcn_readlane(w_incl, 63);
+        TETRI_MARK(8);
+        // the padding rows, shared by the G workgroups of the group
+        zero_padding_rows<D>(p, grp, widx, G, tid, NT);
+        Gp = min(G, W);
+        if (widx >= Gp) return;
+        // (the divisions run on the vector unit: their results are marked as the wave-uniform values they are)
+        // and the host has checked that no product below reaches 2^31)
+        pos = __builtin_amdgcn_readfirstlane((int)((uint32_t)(widx * W) / (uint32_t)Gp));
+        b1 = __builtin_amdgcn_readfirstlane((int)((uint32_t)((widx + 1) * W) / (uint32_t)Gp));
+        const unsigned long long owner = __builtin_amdgcn_ballot_w64(pos >= w_incl - wk && pos < w_incl);
+        if (owner == 0) return;                      // cannot happen for well-formed metadata
+        const int o = __builtin_ctzll(owner);
+        seg.s = o;
+        seg.seg_cu = __builtin_amdgcn_readlane(a, o);
+        seg.n_s = __builtin_amdgcn_readlane(n, o);
+        seg.L = __builtin_amdgcn_readlane(ctx_len, o);
+        nt = __builtin_amdgcn_readlane(ntl, o);
+        const int cs = __builtin_amdgcn_readlane(csl, o);
+        page = __builtin_amdgcn_readlane(pg, o);
+        page_hi = __builtin_amdgcn_readlane(pg_hi, o);
+        const int seg_lin = __builtin_amdgcn_readlane(w_incl - wk, o);
+        const int x = pos - seg_lin;
+        // the tile of the segment position x falls into: the last one that starts at or before x
+        j = 0;
+        for (int j0 = 0; j0 < nt; j0 += 64) {
+            const int cand = j0 + lane;
+            const bool ok = cand < nt && cand * cs + new_stages_before<STAGE>(cand, bm_shift) <= x;
+            const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok));
+            if (cnt == 0) break;
+            j = j0 + cnt - 1;
+            if (cnt < 64) break;
+        }
+        tile_lin = seg_lin + j * cs + new_stages_before<STAGE>(j, bm_shift);
+        tile_index = __builtin_amdgcn_readlane(t_incl - ntl, o) + j;
     }
+
+    // a job of stream mode from the cursor (seg, j, tile_lin, tile_index, pos); moves the cursor behind it
+    auto stream_job = [&](Job &X) __attribute__((always_inline)) {
+        X.seg_cu = seg.seg_cu; X.n_s = seg.n_s; X.t0 = j << bm_shift; X.tile_index = tile_index;
+        X.src = make_src<D, KS>(p, kh, seg, X.t0);
+        const int n_all = X.src.n_ctx_tiles + (X.src.n_new + STAGE - 1) / STAGE;
+        const int tile_end = tile_lin + n_all;
+        X.it_begin = pos - tile_lin;
+        X.it_end = min(b1, tile_end) - tile_lin;
+        X.wf = __builtin_amdgcn_readfirstlane((int)((uint32_t)((tile_lin + 1) * Gp - 1) / (uint32_t)W));
+        const int wl = __builtin_amdgcn_readfirstlane((int)((uint32_t)(tile_end * Gp - 1) / (uint32_t)W));
+        X.npieces = wl - X.wf + 1;
+        X.piece = widx - X.wf;
+        pos = tile_lin + X.it_end;
+        if (pos == tile_end) {
+            tile_lin = tile_end;
+            ++tile_index;
+            if (++j >= nt) {
+                j = 0;
+                if (seg.s + 1 < S) {
+                    const int4 e = seg_tab[seg.s + 1];
+                    ++seg.s;
+                    seg.seg_cu = __builtin_amdgcn_readfirstlane(e.x);
+                    seg.n_s = __builtin_amdgcn_readfirstlane(e.y);
+                    seg.L = __builtin_amdgcn_readfirstlane(e.z);
+                    nt = (seg.n_s + BM - 1) >> bm_shift;
+                }
+            }
+        }
+    };
+    if (G != 0) stream_job(J);
+    TETRI_MARK(9);
+
+    // ---- the first job's first stage and its Q rows.  The wavefronts of key part 0 reach this point
+    // first (the older wavefront of a SIMD is served first), so they issue the loads of their partner
+    // in part 1 as well.
+    static_assert(kBNW * KS / kPage == kSlots * KS, "stage 0: wavefront w loads page w of the segment");
+    Carry<D> cy;
+    cy.par = J.it_begin & 1;                         // the first stage goes to buffer 0
+    {
+        const int new_row_bytes = p.Hkv * D * 2;
+        LaneOffsets<D> lo;
+        init_lane_offsets<D>(lo, lane, new_row_bytes);
+        // entry e of the job's block-table row (clamped entries are never used)
+        auto row_entry = [&](int e) -> int {
+            e = min(e, p.max_blocks - 1);
+            if (row_in_lanes) return e < 64 ? __builtin_amdgcn_readlane(bt_lo, e) : __builtin_amdgcn_readlane(bt_hi, e - 64);
+            return ((const const_i32 *)(uintptr_t)(p.bt + J.src.bt_off))[e];
+        };
+        constexpr int PPS = kBNW * KS / kPage;           // pages per stage
+        if (kq == 0) {
+            if (J.it_begin != 0) {                       // the lookup fetched the pages of stage 0
+                page = row_entry(J.it_begin * PPS + wave);
+                page_hi = row_entry(J.it_begin * PPS + wave + kSlots);
+            }
+            StageLoads sl;
+#pragma unroll
+            for (int part = 0; part < KS; ++part) {
+                const bool full = describe_stage_loads<D, KS>(J.src, ws, lo, part == 0 ? page : page_hi, J.it_begin, wave + part * kSlots,
+                                                              new_row_bytes, lds_address(smem), sl);
+                issue_stage_loads<D, KS>(sl, full, lane);
+            }
+        }
+        cy.page = row_entry((J.it_begin + 1) * PPS + wave);
+        const int hh = slot & (p.hpw - 1), rbk = slot >> p.hpw_shift;
+        request_q<D>(p, J, grp * p.hpw + hh, rbk, lane, cy.qf);
+    }
+    TETRI_MARK(1);
+
     Handover ho;
-    for (int i = 0; i < count + extra; ++i) {
-        if (i != 0) __syncthreads();                 // the stage buffers change hands
-        // only the hand-over of a helper's first tile is left open while it does its second one
-        tile_job<D, KS>(p, i == 0, &params, smem, Mstat, peek, grp, i < count ? first - i : T - 1, piece, ho, i + 1 < count);
+    int guard = p.tiles + 2;                         // a workgroup never has more jobs than the chunk has tiles: malformed metadata cannot keep it here
+    for (bool first = true;; first = false) {
+        const bool more = G != 0 && pos < b1 && --guard > 0;
+        Job N = J;
+        if (more) stream_job(N);
+        tile_job<D, KS>(p, first, &params, smem, Mstat, peek, grp, J, more, N, ws, cy, ho);
+        if (!more) break;
+        J = N;
     }
-    // ---- a helper's first tile whose hand-over was left open: if the other piece has arrived in the
-    // meantime (it found the counter at 0 and went away), this wavefront finishes the tile from its
-    // own stored partial result.
+    // ---- a piece whose hand-over was left open: if it was the last of its tile to arrive, this
+    // wavefront finishes the tile from the partial results in the scratch memory (its own included).
     if (ho.unit >= 0) {
         constexpr int DBLK = D / 32;
-        constexpr size_t UNIT_BYTES = (size_t)DBLK * 4 * 64 * 16 + 2 * 32 * 4;
         asm volatile("" ::: "memory");
         const AttnParams pd = read_params(&params);
-        const int lane = threadIdx.x & 63;
-        if (!ho.announced) {                         // the second job ended before its first barrier
+        if (!ho.announced) {                         // not reached: every job has a stage, whose barrier announces
             wait_vm<0>();
             if (lane == 0) ho.old = atomicAdd(pd.counters + ho.unit, 1);
         }
-        if (__builtin_amdgcn_readfirstlane(ho.old) != 0) {
-            if (lane == 0) pd.counters[ho.unit] = 0;
-            const size_t units = (size_t)pd.groups * pd.tiles * kSlots;
-            const char *mine = pd.scratch + (units + ho.unit) * UNIT_BYTES;          // piece 1
-            const char *other = pd.scratch + (size_t)ho.unit * UNIT_BYTES;           // piece 0
-            f32x4 x[DBLK * 4];
-            float m, l;
-            load_partial(reinterpret_cast<const f32x4 *>(mine) + lane, reinterpret_cast<const float *>(mine + (size_t)DBLK * 4 * 64 * 16) + (lane & 31), x, m, l);
+        if (__builtin_amdgcn_readfirstlane(ho.old) == ho.npieces - 1) {
             f32x16 o[DBLK];
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] = x[db * 4 + v / 4][v % 4];
-            const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), slot = wave % kSlots;
+                for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
             const int head = grp * pd.hpw + (slot & (pd.hpw - 1));
             const int t = ho.t0 + 32 * (slot >> pd.hpw_shift) + (lane & 31);
-            merge_pieces_and_store<D>(o, m, l, other, 1, lane, t < ho.n_s, pd.out + ((size_t)(ho.seg_cu + t) * pd.Hq + head) * D);
+            finish_tile<D>(pd, grp, ho.wf, ho.npieces, -1, slot, o, 0.f, 0.f, lane, t < ho.n_s,
+                           pd.out + ((size_t)(ho.seg_cu + t) * pd.Hq + head) * D);
         }
     }
+    TETRI_MARK(7);
 }
 
 template <int D, int KS>

@@ -76,9 +76,12 @@ tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
     tetri_ctx *h = new (std::nothrow) tetri_ctx;
     if (!h) return fail(nullptr, TETRI_ERR_NOMEM, "tetri_create: out of host memory");
     h->cfg = *c;
-    // Scratch memory for launches that split key ranges: such a launch has at most one workgroup
-    // per CU, 4 (row block, head) slots each, two pieces per slot; a piece is O (32 x head_dim
-    // floats), m and the row sum.
+    // Scratch memory for launches that divide the stages of a head group evenly over workgroups: such
+    // a launch has at most one workgroup per CU, 4 (row block, head) slots each, and a workgroup leaves at
+    // most two partial results per slot (its first and its last job); a partial result is O (32 x head_dim
+    // floats), m and the row sum.  Arrival counters: one per (head group, row tile, slot), fewer than two
+    // tiles per CU in such a launch; two sets, because every such launch uses one set and zeroes the other
+    // for the launch after it.
     hipDeviceProp_t prop;
     if ((e = hipGetDevice(&h->device)) != hipSuccess || (e = hipGetDeviceProperties(&prop, h->device)) != hipSuccess) {
         delete h;
@@ -87,9 +90,10 @@ tetri_status tetri_create(const tetri_config *c, tetri_ctx **out)
     h->num_cus = prop.multiProcessorCount;
     h->scratch_units = (size_t)h->num_cus * 4;
     h->unit_bytes = (size_t)32 * c->head_dim * 4 + 2 * 32 * 4;
+    h->n_counters = (int32_t)(2 * h->scratch_units);
     if ((e = hipMalloc(reinterpret_cast<void **>(&h->scratch), 2 * h->scratch_units * h->unit_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void **>(&h->counters), h->scratch_units * sizeof(int32_t))) != hipSuccess ||
-        (e = hipMemset(h->counters, 0, h->scratch_units * sizeof(int32_t))) != hipSuccess) {
+        (e = hipMalloc(reinterpret_cast<void **>(&h->counters), 2 * (size_t)h->n_counters * sizeof(int32_t))) != hipSuccess ||
+        (e = hipMemset(h->counters, 0, 2 * (size_t)h->n_counters * sizeof(int32_t))) != hipSuccess) {
         tetri_destroy(h);
         return fail(nullptr, TETRI_ERR_HIP, "tetri_create: scratch memory: %s", hipGetErrorString(e));
     }
@@ -119,14 +123,9 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         ctx->split_keys = value;
         return TETRI_OK;
     }
-    if (std::strcmp(key, "split_min_stages") == 0) {
-        if (value < 2) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_min_stages=%d (at least 2)", value);
-        ctx->split_min_stages = value;
-        return TETRI_OK;
-    }
-    if (std::strcmp(key, "split_bias_stages") == 0) {
-        if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_bias_stages=%d (not negative)", value);
-        ctx->split_bias_stages = value;
+    if (std::strcmp(key, "stream_wgs") == 0) {
+        if (value < 0 || value > 255) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: stream_wgs=%d (0..255)", value);
+        ctx->stream_wgs = value;
         return TETRI_OK;
     }
     if (std::strcmp(key, "decode_parts") == 0) {
@@ -137,11 +136,6 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
     if (std::strcmp(key, "transfer_slabs") == 0) {
         if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: transfer_slabs=%d (>= 0)", value);
         ctx->transfer_slabs = value;
-        return TETRI_OK;
-    }
-    if (std::strcmp(key, "split_share_q8") == 0) {
-        if (value < 1 || value > 128) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_share_q8=%d (1..128)", value);
-        ctx->split_share_q8 = value;
         return TETRI_OK;
     }
     if (std::strcmp(key, "attn_variant") == 0) {
@@ -389,64 +383,81 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     // while masked scores (-inf) still map to weight 0
     p.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     p.neg = scale < 0.f;
-    {
-        wave_grouping(p.g, &p.hpw, &p.rb);
-        p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
-        // A launch whose tiles would occupy at most two thirds of the CUs gets one more workgroup
-        // per two tiles: it takes the last third of their key ranges, which shortens the longest
-        // workgroup by a third.
-        // The last tile of the bound and its helper exist only in chunks with ragged segments and
-        // are not counted.
-        const int groups = p.Hq / p.hpw;
-        p.helpers = p.tiles / 2 + 1;
-        if (!h->split_keys || (p.tiles - 1 + p.helpers - 1) * groups > h->num_cus || p.tiles < 2 ||
-            (size_t)p.tiles * groups * 4 > h->scratch_units)
-            p.helpers = 0;
-        if (p.helpers) {
-            // the scratch memory lives on the device the handle was created on
-            int dev = -1;
-            if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
-                return fail(h, TETRI_ERR_INVALID_ARG, "%s: the current device is %d, the handle was created on device %d", fn, dev, h->device);
-        }
-        p.gpx = (groups + 7) / 8;
-        // with helpers the bound's last tile and its helper are extra jobs of existing workgroups
-        p.attn_grid = 8 * p.gpx * (p.helpers ? p.tiles + p.helpers - 2 : p.tiles);
-        p.attn_first = p.attn_grid;
-        // fused append: a few dozen workgroups, each copying every 64th row of the chunk
-        // (every workgroup of this kernel occupies a whole CU: in a launch that splits key ranges only
-        // the CUs its attention workgroups leave free take append workgroups right away)
-        int append_wgs = 64;
-        if (p.helpers) {
-            const int idle = h->num_cus - p.attn_first;
-            append_wgs = idle >= 8 ? (idle < 64 ? idle / 8 * 8 : 64) : 8;
-        }
-        p.append_blocks = kv_pages_w ? (p.C < append_wgs ? p.C : append_wgs) : 0;
-    }
-    // divisions the kernel does by launch constants, as multiplications
-    auto magic = [](uint32_t d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
-    auto log2i = [](int v) { int s = 0; while ((1 << s) < v) ++s; return s; };
-    p.hpw_shift = log2i(p.hpw);
-    p.rb_shift = log2i(p.rb);
-    p.groups = p.Hq / p.hpw;
-    p.gpx_magic = magic((uint32_t)p.gpx);
-    p.tail_q8 = p.helpers ? h->split_share_q8 : 0;
-    p.split_min = h->split_min_stages;
-    p.split_bias = h->split_bias_stages;
-    p.scratch = h->scratch;
-    p.counters = h->counters;
-    p.kv_magic = magic((uint32_t)(p.g / p.hpw));
-    if ((uint64_t)p.attn_grid * (uint64_t)(p.tiles + p.helpers) >= 0x100000000ull)
-        return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
+    wave_grouping(p.g, &p.hpw, &p.rb);
+    const int groups = p.Hq / p.hpw;
+    const int cus = std::max(h->num_cus, 1);
     // Workgroup size of the shared-tile kernel.  A full chunk has at least C / (rows of a tile) tiles per head
     // group; when that alone gives two workgroups per compute unit, four-wavefront workgroups (two to a CU, their
     // barriers independent of each other) run the block loop 4-15 % faster than eight-wavefront ones; on smaller
     // launches the eight-wavefront workgroup, which puts twice the wavefronts on its tile's CU, is the better one.
     int key_parts = h->attn_variant == 1 ? 1 : 2;
-    if (h->attn_variant == 0 && p.helpers == 0 &&
-        (int64_t)(p.C / (32 * p.rb)) * p.groups >= 2 * (int64_t)std::max(h->num_cus, 1))
-        key_parts = 1;
-    hipError_t e = tetri_launch_attn(h, p, key_parts, static_cast<hipStream_t>(stream));
+    if (h->attn_variant == 0 && h->stream_wgs == 0 && (int64_t)(p.C / (32 * p.rb)) * groups >= 2 * (int64_t)cus) key_parts = 1;
+    p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
+    p.gpx = (groups + 7) / 8;
+    // Stream mode: a launch with fewer than two row tiles per compute unit gives every head group G workgroups
+    // that share the stages of all its tiles evenly (one workgroup per compute unit, a few units left to the
+    // fused append).  The division is worked out on the device from the segment lengths; the host only has to
+    // know that its numbers fit: at most 64 segments (one lane each), positions and their products with G in 31
+    // bits, scratch memory and arrival counters for every (workgroup, slot) and (tile, slot).
+    int G = 0;
+    if (h->stream_wgs > 0) G = h->stream_wgs;
+    else if (h->split_keys && (int64_t)p.tiles * groups < 2 * (int64_t)cus) G = std::min(255, (cus - (kv_pages_w ? 8 : 0)) / groups);
+    const int stage = 64 * key_parts;
+    const int64_t stage_bound = (int64_t)p.tiles * (((int64_t)p.max_blocks * 16 + p.C) / stage + 2);
+    if (G > 0 && (p.S > 64 || stage_bound * (G + 1) >= 0x7fffffffll || (size_t)groups * G * 4 > h->scratch_units ||
+                  (int64_t)groups * p.tiles * 4 > h->n_counters))
+        G = 0;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    // (a stream that is being captured into a graph takes no event queries or records: the graph orders its nodes)
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing = G > 0 && (hipStreamIsCapturing(hs, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone);
+    if (G > 0) {
+        // the scratch memory lives on the device the handle was created on
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+            return fail(h, TETRI_ERR_INVALID_ARG, "%s: the current device is %d, the handle was created on device %d", fn, dev, h->device);
+        // such launches share the handle's scratch memory and counters: one on another stream must not start
+        // before the previous one has ended.  (Asked of the stream, not of an event behind the launch: recording
+        // an event per launch costs several microseconds of queue time between 20-us kernels.)
+        if (!capturing && h->divide_launched && h->last_divide_stream != hs && hipStreamQuery(h->last_divide_stream) == hipErrorNotReady)
+            return fail(h, TETRI_ERR_INVALID_ARG, "%s: the stream of this handle's previous launch that uses its scratch memory still has work "
+                        "pending; launches on one handle must not overlap (use one handle per stream)", fn);
+    }
+    p.stream_wgs = G;
+    p.attn_grid = 8 * p.gpx * (G > 0 ? G : p.tiles);
+    p.attn_first = p.attn_grid;
+    // fused append: a few dozen workgroups, each copying every 64th row of the chunk
+    // (every eight-wavefront workgroup of this kernel occupies a whole CU: in stream mode only the CUs the
+    // attention workgroups leave free take append workgroups right away)
+    int append_wgs = 64;
+    if (G > 0) {
+        const int idle = cus - p.attn_first;
+        append_wgs = idle >= 8 ? (idle < 64 ? idle / 8 * 8 : 64) : 8;
+    }
+    p.append_blocks = kv_pages_w ? (p.C < append_wgs ? p.C : append_wgs) : 0;
+    // divisions the kernel does by launch constants, as multiplications
+    auto magic = [](uint32_t d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
+    auto log2i = [](int v) { int s = 0; while ((1 << s) < v) ++s; return s; };
+    p.hpw_shift = log2i(p.hpw);
+    p.rb_shift = log2i(p.rb);
+    p.groups = groups;
+    p.gpx_magic = magic((uint32_t)p.gpx);
+    p.scratch = h->scratch;
+    p.n_counters = h->n_counters;
+    p.counters = h->counters + (size_t)h->counter_set * h->n_counters;
+    p.counters_next = h->counters + (size_t)(1 - h->counter_set) * h->n_counters;
+    p.kv_magic = magic((uint32_t)(p.g / p.hpw));
+    if ((uint64_t)p.attn_grid * (uint64_t)(p.tiles + G + 1) >= 0x100000000ull)
+        return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
+    hipError_t e = tetri_launch_attn(h, p, key_parts, hs);
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
+    if (G > 0) {
+        h->counter_set = 1 - h->counter_set;
+        if (!capturing) {
+            h->last_divide_stream = hs;
+            h->divide_launched = true;
+        }
+    }
     return TETRI_OK;
 }
 

@@ -10,17 +10,19 @@ struct tetri_ctx {
     tetri_config cfg;
     std::string err;
     int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts
-    int split_keys = 1;     // 1 = launches that would leave a third of the CUs idle split the key ranges of their tiles
-    int split_min_stages = 8;   // ... those of at least this many stages
-    int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
-    int split_share_q8 = 85;    // the share of the remaining stages a tile hands over, in 1/256 (a third)
+    int split_keys = 1;     // 1 = launches with fewer than two row tiles per CU divide the stages of every head group evenly over the CUs
+    int stream_wgs = 0;     // workgroups per head group of such a launch (0: as many as the device has CUs for); > 0 forces the mode
     int decode_parts = 0;       // key parts per (request, kv head) of the decode kernel (0: the library chooses)
     int transfer_slabs = 0;     // (K / V, head) slabs per workgroup of the export / import kernels (0: the library chooses)
     int device = 0;         // the device the handle was created on; its scratch memory lives there
     int num_cus = 0;
-    char *scratch = nullptr;        // partial results of split tiles: 2 pieces x scratch_units units
-    int32_t *counters = nullptr;    // scratch_units arrival counters, zero between launches
+    char *scratch = nullptr;        // partial results of tiles shared by workgroups: 2 x scratch_units units
+    int32_t *counters = nullptr;    // two sets of n_counters arrival counters: a launch uses one and zeroes the other
     size_t scratch_units = 0, unit_bytes = 0;
+    int32_t n_counters = 0;
+    int counter_set = 0;            // the set the next dividing launch uses
+    bool divide_launched = false;       // a launch has used scratch and counters ...
+    hipStream_t last_divide_stream = nullptr;   // ... the last one on this stream
     float *static_scratch = nullptr;    // this device's address of the library's static scratch array (decode parts)
     size_t static_scratch_bytes = 0;
 };
@@ -39,14 +41,13 @@ struct AttnParams {
     int32_t rb;           // 32-row blocks handled by one workgroup
     int32_t hpw_shift, rb_shift;   // log2 of the two
     int32_t groups;       // Hq / hpw: head groups, one workgroup column each
-    int32_t helpers;      // per head group: workgroups that take the last third of two tiles' key ranges (0: no split)
-    int32_t tail_q8;      // the share of a tile's stages that goes to its helper, in 1/256 (0: no split)
-    int32_t split_min;    // only key ranges of at least this many stages are split
-    int32_t split_bias;   // stages not counted when a key range's last third is measured
+    int32_t stream_wgs;   // workgroups per head group that share its stages evenly (0: one workgroup per row tile)
+    int32_t n_counters;   // size of a set of arrival counters
     int32_t gpx;          // head groups per XCD
     uint32_t gpx_magic;   // ceil(2^32 / gpx), 0 for 1
-    char *scratch;        // partial results of split tiles
-    int32_t *counters;    // one per (group, tile, slot), all zero between launches
+    char *scratch;        // partial results of tiles shared by several workgroups
+    int32_t *counters;    // one per (group, tile, slot), all zero when the launch begins
+    int32_t *counters_next;   // the set of the next such launch: zeroed by this one
     uint32_t kv_magic;    // the same for g / hpw: head group -> kv head
     int32_t max_blocks;
     int32_t tiles;        // upper bound of the number of row tiles of the chunk

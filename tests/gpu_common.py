@@ -22,14 +22,16 @@ def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_c
     """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
     sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                           w.num_pages, tables, device=DEV, page_size=w.page_size)
-    # variants 10 / 11 / 13: kernels 0 / 1 / 0 with every key range of two or more stages split between
-    # two workgroups (the library itself only splits long ones); 12: kernel 0, never split
-    sess.handle.tetri_set_option("attn_variant", variant if variant < 10 else (1 if variant == 11 else 0))
-    if variant in (10, 11, 13):
-        sess.handle.tetri_set_option("split_min_stages", 2)
-        sess.handle.tetri_set_option("split_bias_stages", 0)
-    if variant == 13:       # half of every key range handed over: helpers settle their first tile late
-        sess.handle.tetri_set_option("split_share_q8", 128)
+    # variants 0 / 1 / 2: the library's choice / 4-wavefront / 8-wavefront workgroups, each with the library's
+    # choice of how the work is handed out (small launches: the stages of a head group divided evenly over as many
+    # workgroups as the device has compute units for, i.e. many pieces per tile); 10 / 11: 8- / 4-wavefront
+    # workgroups with 5 workgroups per head group; 13: with 2 (every workgroup runs many jobs); 12: one workgroup per
+    # row tile, never divided
+    sess.handle.tetri_set_option("attn_variant", variant if variant < 10 else (1 if variant == 11 else 2))
+    if variant in (10, 11):
+        sess.handle.tetri_set_option("stream_wgs", 5)
+    if variant == 13:
+        sess.handle.tetri_set_option("stream_wgs", 2)
     if variant == 12:
         sess.handle.tetri_set_option("split_keys", 0)
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)

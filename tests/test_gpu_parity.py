@@ -13,13 +13,14 @@ import gpu_common as gc
 
 pytestmark = pytest.mark.gpu
 
-# attention kernel variants: 0 = library's choice, 1 / 2 = shared-tile kernel with 4 / 8 wavefronts;
-# 10 / 11 = kernels 0 / 1 handing the last third of every key range of two or
-# more stages to a second workgroup (13: half of it), 12 = kernel 0 never doing so.  Every variant must meet the same bar.
+# attention kernel variants: 0 = library's choice, 1 / 2 = 4- / 8-wavefront workgroups (small launches divide the
+# stages of each head group evenly over many workgroups, whose partial results of shared tiles are merged);
+# 10 / 11 = 8- / 4-wavefront workgroups with five workgroups per head group, 13 = with two (many jobs per
+# workgroup), 12 = one workgroup per row tile, nothing divided.  Every variant must meet the same bar.
 VARIANTS = [0, 1, 2, 10, 11, 12, 13]
 
 
-@pytest.fixture(params=VARIANTS, ids=["auto", "tile4", "tile2", "handover", "handover4", "whole", "handover-half"])
+@pytest.fixture(params=VARIANTS, ids=["auto", "wave4", "wave8", "stream5", "stream5-wave4", "whole", "stream2"])
 def variant(request):
     return request.param
 
@@ -75,7 +76,7 @@ def test_append_before_attention_gives_same_result(oracle, variant):
     assert torch.equal(pool_a.view(torch.int16), pool_b.view(torch.int16))
 
 
-@pytest.mark.parametrize("fused_variant", [0, 1, 2], ids=["auto", "tile4", "tile2"])
+@pytest.mark.parametrize("fused_variant", [0, 1, 2], ids=["auto", "wave4", "wave8"])
 @pytest.mark.parametrize("name", ["mid-page-starts", "ragged-tiles", "gqa4", "one-token-segments", "partial-last-chunk", "many-tiles"])
 def test_fused_attention_append_equals_two_calls(oracle, name, fused_variant):
     """tetri_chunk_prefill_attn_append == tetri_chunk_prefill_attn then tetri_kv_append, bit for bit, also with the

@@ -63,7 +63,7 @@ constexpr int kBNW = 64;      // keys per wavefront per stage
 template <int D>
 struct LaneOffsets {
     uint32_t k_ctx, v_ctx;      // rows 512 (256) bytes apart inside a (page, head) block of the pool
-    uint32_t k_new, v_new;      // rows Hkv*D*2 bytes apart in k_new / v_new
+    uint32_t new_extra;         // what a lane's row is further away in k_new / v_new, whose rows are Hkv*D*2 bytes apart
 };
 
 template <int D>
@@ -75,8 +75,7 @@ __device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane, 
     const int vc = (lane % CH) ^ v_swizzle<D>(r0);
     lo.k_ctx = r0 * D * 2 + kc * 16;
     lo.v_ctx = r0 * D * 2 + vc * 16;
-    lo.k_new = r0 * new_row_bytes + kc * 16;
-    lo.v_new = r0 * new_row_bytes + vc * 16;
+    lo.new_extra = r0 * (new_row_bytes - D * 2);
 }
 // XOR that turns instruction 0's chunk into instruction i's (in bytes).
 template <int D> __host__ __device__ __forceinline__ constexpr uint32_t k_inst_xor(int i)
@@ -106,6 +105,20 @@ struct Job {
     JobSrc src;
 };
 
+// One of two jobs, chosen field by field (a choice between the addresses of two jobs would keep both in memory).
+__device__ __forceinline__ Job pick(bool first, const Job &a, const Job &b)
+{
+    Job r;
+    r.seg_cu = first ? a.seg_cu : b.seg_cu; r.n_s = first ? a.n_s : b.n_s; r.t0 = first ? a.t0 : b.t0;
+    r.tile_index = first ? a.tile_index : b.tile_index;
+    r.it_begin = first ? a.it_begin : b.it_begin; r.it_end = first ? a.it_end : b.it_end;
+    r.piece = first ? a.piece : b.piece; r.npieces = first ? a.npieces : b.npieces; r.wf = first ? a.wf : b.wf;
+    r.src.bt_off = first ? a.src.bt_off : b.src.bt_off; r.src.new_off = first ? a.src.new_off : b.src.new_off;
+    r.src.L = first ? a.src.L : b.src.L; r.src.n_new = first ? a.src.n_new : b.src.n_new;
+    r.src.n_ctx_tiles = first ? a.src.n_ctx_tiles : b.src.n_ctx_tiles;
+    return r;
+}
+
 // Wave-uniform pieces of a wavefront's load addresses that no job changes.
 struct WaveSrc {
     const int32_t *bt;          // the block table
@@ -117,6 +130,22 @@ struct WaveSrc {
     uint32_t wave_new_bytes;    // a wavefront's 16 rows
     int max_blocks;
 };
+
+template <int D, int KS>
+__device__ __forceinline__ WaveSrc make_wave_src(const AttnParams &p, int kh)
+{
+    WaveSrc ws;
+    ws.bt = p.bt;
+    ws.new_k = reinterpret_cast<const char *>(p.k_new);
+    ws.new_v = reinterpret_cast<const char *>(p.v_new);
+    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * (kPage * D * 2);
+    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
+    ws.v_delta = p.Hkv * (kPage * D * 2);
+    ws.stage_new_bytes = (kBNW * KS) * (p.Hkv * D * 2);
+    ws.wave_new_bytes = 16 * (p.Hkv * D * 2);
+    ws.max_blocks = p.max_blocks;
+    return ws;
+}
 
 // The direct-to-LDS loads of this wavefront's 16 rows of one stage (K and V): one scalar base per
 // matrix; the NI instructions of a matrix differ only in their per-lane offsets.
@@ -140,8 +169,8 @@ __device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const Wa
     sl.j0 = (ctx ? it : jn) * STAGE + 16 * wave;
     sl.limit = ctx ? src.L : src.n_new;
     sl.kdst = k_lds + wave * (16 * D * 2);
-    sl.ko = ctx ? lo.k_ctx : lo.k_new;
-    sl.vo = ctx ? lo.v_ctx : lo.v_new;
+    sl.ko = lo.k_ctx + (ctx ? 0u : lo.new_extra);
+    sl.vo = lo.v_ctx + (ctx ? 0u : lo.new_extra);
     // pool rows of an instruction follow the previous one's directly (the immediate offset covers
     // it); rows of k_new / v_new are `step` bytes further apart than that
     if (ctx) {
@@ -271,11 +300,10 @@ __device__ __forceinline__ AttnParams read_params(const AttnParams *lds_copy)
 // what a wavefront remembers of it while it goes on with the workgroup's next job (see tile_job).
 struct Handover {
     int unit = -1;          // arrival counter of the (head group, tile, slot); -1: nothing pending
-    int old = 0;            // lane 0: what the counter held when this piece was announced
-    bool announced = false;
+    bool announced = false; // what the counter held then is kept in LDS (old_stash)
     bool fresh = false;     // the partial result's stores are the wavefront's most recent memory operations
     int seg_cu = 0, t0 = 0, n_s = 0;    // where the tile's rows are
-    int npieces = 0, wf = 0;
+    int npieces = 0, wf = 0, tile_index = 0;
 };
 
 // Byte size of one wavefront's partial result in the scratch memory: O (32 rows x D floats in the
@@ -289,25 +317,31 @@ template <int D> constexpr size_t unit_bytes() { return (size_t)(D / 32) * 4 * 6
 // Where piece i of a tile keeps its partial result: a workgroup has two places, one for a piece
 // that is not the first of its tile (only a workgroup's first job can be one) and one for a first
 // piece (only its last job can be an unfinished one).
+// In tail mode (two pieces per tile, found by the tile's index) piece i of every tile has a region of its own.
 template <int D>
-__device__ __forceinline__ char *piece_scratch(const AttnParams &p, int grp, int wf, int i, int slot)
+__device__ __forceinline__ char *piece_scratch(const AttnParams &p, int grp, int wf, int tile_index, int i, int slot)
 {
-    const size_t unit = (((size_t)grp * p.stream_wgs + wf + i) * 2 + (i == 0 ? 1 : 0)) * kSlots + slot;
+    const size_t unit = p.stream_wgs != 0 ? (((size_t)grp * p.stream_wgs + wf + i) * 2 + (i == 0 ? 1 : 0)) * kSlots + slot
+                                          : (((size_t)i * p.groups + grp) * p.tiles + tile_index) * kSlots + slot;
     return p.scratch + unit * unit_bytes<D>();
 }
 
 // All pieces of a tile are there: merge them, normalise, write the rows.  `mine` is the piece this
-// wavefront still holds in registers (o, m, l), or -1 when all of them are read from the scratch
-// memory.  Whoever calls this, the value is the same: the pieces are combined one after the other
+// wavefront has not written to the scratch memory: its O is in LDS at `own` (parked there so that the
+// merge holds two copies of O in registers, not three), its m and row sum in (m, l); -1 when all
+// pieces are read from the scratch memory.  Whoever calls this, the value is the same: the pieces are combined one after the other
 // in piece order, each step bringing the running result and the next piece to their common
 // reference exponent: acc = acc * 2^(m_acc - m') + O_i * 2^(m_i - m'), m' = max(m_acc, m_i).
 // One pass over the scratch memory: a piece's O, m and row sum arrive in one round trip.
 template <int D>
-__device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf, int npieces, int mine, int slot, f32x16 (&o)[D / 32], float m,
-                                            float l, int lane, bool row_ok, uint16_t *orow)
+__device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf, int tile_index, int npieces, int mine, int slot,
+                                            const f32x4 *own, float m, float l, int lane, bool row_ok, int row, int head)
 {
     constexpr int DBLK = D / 32;
     constexpr size_t STATS = (size_t)DBLK * 4 * 64 * 16;
+#ifdef TETRI_EXP_NOFINISH
+    return;
+#endif
     const int half = lane >> 5, l32 = lane & 31;
     float macc = 0.f, lacc = 0.f;
     f32x16 acc[DBLK];
@@ -321,11 +355,9 @@ __device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf
         if (i == mine) {
             mi = m; li = l;
 #pragma unroll
-            for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) x[db * 4 + v / 4][v % 4] = o[db][v];
+            for (int u = 0; u < DBLK * 4; ++u) x[u] = own[u * 64 + lane];
         } else {
-            const char *src = piece_scratch<D>(p, grp, wf, i, slot);
+            const char *src = piece_scratch<D>(p, grp, wf, tile_index, i, slot);
             load_partial(reinterpret_cast<const f32x4 *>(src) + lane, reinterpret_cast<const float *>(src + STATS) + l32, x, mi, li);
         }
         if (i == 0) {
@@ -347,6 +379,7 @@ __device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf
     }
     if (!row_ok) return;
     const float inv = __builtin_amdgcn_rcpf(lacc);
+    uint16_t *orow = p.out + ((size_t)row * p.Hq + head) * D;     // (worked out here: a pointer kept across the loop above costs two registers)
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -354,6 +387,41 @@ __device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf
             bf16x4 w;
 #pragma unroll
             for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[db][q4 * 4 + e] * inv);
+            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
+        }
+}
+
+// The same for a tile of two pieces, of which this wavefront holds one (`piece`) in registers: one round trip for the
+// other piece, no copy of O besides the two.  Bit for bit what finish_tile computes for two pieces.
+template <int D>
+__device__ __forceinline__ void finish_pair(const AttnParams &p, int grp, int wf, int tile_index, int piece, int slot, f32x16 (&o)[D / 32],
+                                            float m, float l, int lane, bool row_ok, int row, int head)
+{
+    constexpr int DBLK = D / 32;
+    constexpr size_t STATS = (size_t)DBLK * 4 * 64 * 16;
+    const int half = lane >> 5, l32 = lane & 31;
+    const char *other = piece_scratch<D>(p, grp, wf, tile_index, 1 - piece, slot);
+    float m1, l1;
+    f32x4 x[DBLK * 4];
+    load_partial(reinterpret_cast<const f32x4 *>(other) + lane, reinterpret_cast<const float *>(other + STATS) + l32, x, m1, l1);
+    const float mnew = fmaxf(m, m1);
+    const float w_own = __builtin_amdgcn_exp2f(m - mnew), w_oth = __builtin_amdgcn_exp2f(m1 - mnew);
+    // piece 1 joins piece 0: fma(piece 1, its weight, piece 0 * its weight)
+    l = piece == 0 ? __builtin_fmaf(l1, w_oth, l * w_own) : __builtin_fmaf(l, w_own, l1 * w_oth);
+    if (!row_ok) return;
+    const float inv = __builtin_amdgcn_rcpf(l);
+    uint16_t *orow = p.out + ((size_t)row * p.Hq + head) * D;
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
+                const float r = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
+                w[e] = (__bf16)(r * inv);
+            }
             *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
         }
 }
@@ -386,7 +454,7 @@ __device__ __forceinline__ void request_q(const AttnParams &p, const Job &J, int
 // stage are in flight and cy holds its Q fragments; on exit the same holds for `next`.
 template <int D, int KS>
 __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_job, const AttnParams *params, uint4 *smem, float (*Mstat)[2][32],
-                                         uint32_t (*peek)[64], int grp, const Job &J, bool next, const Job &N, const WaveSrc &ws, Carry<D> &cy,
+                                         uint32_t (*peek)[64], int *old_stash, int grp, int kh, const Job &J, bool next, const Job &N, Carry<D> &cy,
                                          Handover &ho)
 {
     constexpr int CH = D / 8;        // 16-byte chunks per K/V row
@@ -403,6 +471,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         asm volatile("" ::: "memory");               // keeps this a branch: the reads are not done speculatively
         p = read_params(params);
     }
+    const WaveSrc ws = make_wave_src<D, KS>(p, kh);
     // The thread id is made opaque per job: values derived from it are then computed where a job
     // needs them instead of being kept in registers across the whole job loop.
     int tid = threadIdx.x;
@@ -439,8 +508,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     bool pend = false;                               // the next stage's loads are described in sl, not issued
     const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
     int page = __builtin_amdgcn_readfirstlane(cy.page);
-    // a job of one stage: the stage after its first one is the next job's first
-    if (it_begin + 1 >= n_stages && next) page = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin, wave);
+    // the pages of this wavefront's rows of the next job's first two stages: asked for now, needed after the loop
+    int page_n0 = 0, page_n1 = 0;
+    if (next) {
+        page_n0 = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin, wave);
+        page_n1 = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin + 1, wave);
+    }
 
     bf16x8 qf[KSTEPS];
 #pragma unroll
@@ -463,37 +536,36 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // (A operand of S^T).  V: for step j (16 keys) and d block db the lane gets keys 16j + 4*half +
     // {0..3, 8..11} of d = 32*db + l32 through two transposing reads (A operand of O^T).
     // The per-lane parts of the addresses (row inside the wavefront's 64-key part, swizzled chunk)
-    // never change: the address of step 0 (K) and of d block 0 (V) is computed once and kept; the
-    // swizzles are XORs of chunk bits that the step / block index leaves alone, so step st is that
-    // address ^ (st << 5) and block db that address ^ (db << 6), one operation at the point of use
-    // instead of a register each for the whole loop.  Stage buffer and block are added as one byte
-    // offset, which is an instruction immediate wherever it is known at compile time.
+    // never change: they are computed once; stage buffer and block are added as one byte offset,
+    // which is an instruction immediate wherever it is known at compile time.
     constexpr int BLOCK_BYTES = 32 * D * 2;            // one 32-key block of K or of V
-    uint32_t kbase0, vbase0;
+    uint32_t kbase[KSTEPS], vbase[DBLK];
     {
         const int r = kq * kBNW + l32;
-        kbase0 = r * D * 2 + ((half ^ k_swizzle<D>(r)) << 4);
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st) kbase[st] = r * D * 2 + (((2 * st + half) ^ k_swizzle<D>(r)) << 4);
         const int rv = kq * kBNW + 4 * half + (i16 >> 2);
-        const int d0 = 16 * (blk & 1) + 4 * (i16 & 3);
-        vbase0 = 2 * STAGE_BYTES + rv * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const int d0 = db * 32 + 16 * (blk & 1) + 4 * (i16 & 3);
+            vbase[db] = 2 * STAGE_BYTES + rv * D * 2 + (((d0 >> 3) ^ v_swizzle<D>(rv)) << 4) + ((d0 & 7) << 1);
+        }
     }
     const char *smem_b = reinterpret_cast<const char *>(smem);
     // byte offset of the stage buffer that holds stage `it` of this job
     auto buf_of = [&](int it) -> int { return ((it & 1) ^ par) * (int)STAGE_BYTES; };
     // off = buffer * STAGE_BYTES + block * BLOCK_BYTES
     auto load_k = [&](bf16x8 (&kf)[KSTEPS], int off) {
-        asm volatile("" : "+v"(kbase0));               // the XORs below stay here: hoisted out of the loop they would be registers again
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st)
-            kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + (kbase0 ^ (st << 5)) + off));
+            kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + kbase[st] + off));
     };
     auto load_v = [&](s16x8 (&vf)[2 * DBLK], int off) {
-        asm volatile("" : "+v"(vbase0));
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int db = 0; db < DBLK; ++db) {
-                const char *a = smem_b + (vbase0 ^ (db << 6)) + off + j * (16 * D * 2);
+                const char *a = smem_b + vbase[db] + off + j * (16 * D * 2);
                 const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
                 const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * D * 2));
                 vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -536,28 +608,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         __syncthreads();
         return stage_blocks(it);
     };
-    // The loads of the stage after `it`: the job's next stage, or after its last stage the first
-    // stage of the workgroup's next job, into the buffer stage `it` does not use.
     auto next_stage_loads = [&](int it, int nb, bool pv_before) {
-        const bool in_job = it + 1 < n_stages;
-        if (in_job || next) {
-            JobSrc from;                                 // field by field: a choice between two addresses would keep both jobs in memory
-            from.bt_off = in_job ? src.bt_off : nsrc.bt_off;
-            from.new_off = in_job ? src.new_off : nsrc.new_off;
-            from.L = in_job ? src.L : nsrc.L;
-            from.n_new = in_job ? src.n_new : nsrc.n_new;
-            from.n_ctx_tiles = in_job ? src.n_ctx_tiles : nsrc.n_ctx_tiles;
-            const int nit = in_job ? it + 1 : n_it_begin;
-            const bool full = describe_stage_loads<D, KS>(from, ws, lo, page, nit, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
+        if (it + 1 < n_stages) {
+            const bool full = describe_stage_loads<D, KS>(src, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
             if (full && pv_before && nb != 0 && load_point != 0) pend = true;
             else issue_stage_loads<D, KS>(sl, full, lane);
-            // the page of the stage after that one (past the end of the next job: never used)
-            if (in_job && it + 2 >= n_stages) {
-                if (next) page = load_stage_page<KS>(ws.bt + nsrc.bt_off, ws.max_blocks, n_it_begin, wave);
-            } else {
-                page = load_stage_page<KS>(ws.bt + from.bt_off, ws.max_blocks, nit + 1, wave);
-            }
         }
+        page = load_stage_page<KS>(ws.bt + src.bt_off, ws.max_blocks, it + 2, wave);
     };
     auto qk = [&](const bf16x8 (&kf)[KSTEPS]) -> f32x16 {
         f32x16 sacc;
@@ -578,18 +635,26 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     int nblk;
     // A partial result left by an earlier job is announced behind a wait for all of this wavefront's memory
     // operations, its stores included.  What the counter held is looked at when the workgroup's jobs are done.
+    // (called behind a wait for all memory operations: the answer to an announcement made at the previous such
+    // point has arrived and is put away)
+    int old = 0;            // lane 0: what the counter held when the piece was announced, until it is put away in LDS
+    bool stashed = true;    // (a register kept across all jobs would be spilled to memory)
     auto announce = [&]() {
+        if (!stashed) {
+            if (lane == 0) old_stash[slot] = old;
+            stashed = true;
+        }
         if (ho.unit >= 0 && !ho.announced) {
-            if (lane == 0) ho.old = atomicAdd(p.counters + ho.unit, 1);
+            if (lane == 0) old = atomicAdd(p.counters + ho.unit, 1);
             ho.announced = true;
+            stashed = false;
         }
     };
     if (ho.unit >= 0 && ho.fresh) {
         // The job before this one left a partial result: its stores were issued after this job's first stage and
         // Q rows were requested, they are this wavefront's most recent memory operations, and they go all the way
         // to memory.  Memory operations complete in the order they were issued: the first stage waits for all but
-        // those stores; the announcement follows at the job's second stage (a job of one stage: at the next job's
-        // first stage, or when the workgroup's jobs are done).
+        // those stores; the announcement follows at the job's second stage (a job of one stage: when its loop is done).
         wait_vm<kPartialStores<D>>();
         __builtin_amdgcn_s_barrier();
         nblk = stage_blocks(it);
@@ -604,9 +669,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         nblk = sync_stage(++it);
         announce();
     }
-    if (nblk == 0) {
-        next_stage_loads(it, 0, false);                // the job's last stage and nothing to do in it: the next job's loads
-    } else {
+    if (nblk != 0) {
         int kb = 0;
         bf16x8 kf[KSTEPS];
         load_k(kf, buf_of(it));
@@ -748,9 +811,20 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             if (!block(s_b, s_a)) break;
         }
     }
-    if (pend) {                                      // the next job's loads, if their issue point was not reached
-        issue_stage_loads<D, KS>(sl, true, lane);
-        pend = false;
+    // ---- the next job's first stage, into the buffer the job's last stage does not use: every wavefront has left it.
+    // The loads travel during this job's epilogue.
+    if (next) {
+        const bool full = describe_stage_loads<D, KS>(nsrc, ws, lo, page_n0, n_it_begin, wave, new_row_bytes,
+                                                      smem_lds + (buf_of(n_stages - 1) ^ STAGE_BYTES), sl);
+        issue_stage_loads<D, KS>(sl, full, lane);
+    }
+    if (ho.unit >= 0 && (!ho.announced || !stashed)) {        // a partial result not announced, or announced at the job's last stage
+        wait_vm<0>();
+        announce();
+        if (!stashed) {
+            wait_vm<0>();
+            announce();
+        }
     }
 
     TETRI_MARK((first_job ? 0 : 12) + 4);
@@ -760,7 +834,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     if (next) {
         request_q<D>(pe, N, head, rbk, lane, cy.qf);
         cy.par = ((n_stages & 1) ^ par) ^ (n_it_begin & 1);      // its first stage goes where stage n_stages of this job would
-        cy.page = page;
+        cy.page = page_n1;
     }
     // ---- merge the KS key parts through LDS: part 1 publishes (m, row sum, O), part 0 finishes.
     // The partial O goes into a stage buffer nobody reads any more.  After a workgroup's last job that
@@ -775,13 +849,16 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // travels while the key parts merge.
     if (pieces && !next && kq == 0 && wave_has_rows) peek_coherent(pe.counters + unit, lds_address(peek[slot]));
     float ltot = half_swap_sum(lsum);
+    // where this wavefront may keep one O (16-byte vector u of lane l at index u * 64 + l): the place of its key-part
+    // partner's partial result, or, with one key part, a quarter of the stage buffers
+    f32x4 *part = reinterpret_cast<f32x4 *>(smem) + slot * (DBLK * 4 * 64);
     if constexpr (KS == 2) {
         static_assert(2 * (DBLK * 16 * 64 * 4) == STAGE_BYTES, "two slots per matrix region");
         if (next) lds_barrier();
         TETRI_MARK((first_job ? 0 : 12) + 10);
         const int dead_off = next ? buf_of(n_stages - 1) : (buf_of(n_stages - 1) ^ (int)STAGE_BYTES);
         char *dead = reinterpret_cast<char *>(smem) + dead_off + (slot >> 1) * (2 * STAGE_BYTES);
-        f32x4 *part = reinterpret_cast<f32x4 *>(dead + (slot & 1) * (DBLK * 16 * 64 * 4));
+        part = reinterpret_cast<f32x4 *>(dead + (slot & 1) * (DBLK * 16 * 64 * 4));
         if (kq == 1) {
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
@@ -812,11 +889,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 for (int e = 0; e < 4; ++e) o[db][q4 * 4 + e] = o[db][q4 * 4 + e] * w0 + x[e] * w1;
             }
     } else {
+        static_assert(kSlots * (DBLK * 4 * 64 * 16) <= 4 * STAGE_BYTES, "an O per wavefront fits the stage buffers");
+        // a tile finished here from several pieces parks O in the stage buffers: every wavefront has left them
+        if (pieces && !next) lds_barrier();
         if (!wave_has_rows) return;
     }
 
     TETRI_MARK((first_job ? 0 : 12) + 11);
-    uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t) * pe.Hq + head) * D;
     // ---- a tile of several pieces.  unit = (head group, tile, slot); its counter starts at 0.
     if (pieces) {
         bool all_there = false;
@@ -826,7 +905,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         }
         if (!all_there) {
             // leave (O, m, row sum) in the scratch memory ...
-            char *mine = piece_scratch<D>(pe, grp, J.wf, J.piece, slot);
+            char *mine = piece_scratch<D>(pe, grp, J.wf, J.tile_index, J.piece, slot);
             f32x4 *po = reinterpret_cast<f32x4 *>(mine);
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
@@ -850,7 +929,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 ho.announced = false;
                 ho.fresh = true;
                 ho.seg_cu = J.seg_cu; ho.t0 = J.t0; ho.n_s = n_s;
-                ho.npieces = J.npieces; ho.wf = J.wf;
+                ho.npieces = J.npieces; ho.wf = J.wf; ho.tile_index = J.tile_index;
                 TETRI_MARK((first_job ? 0 : 12) + 6);
                 return;
             }
@@ -863,7 +942,20 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 return;
             }
         }
-        finish_tile<D>(pe, grp, J.wf, J.npieces, J.piece, slot, o, m, ltot, lane, row_ok, orow);
+        if (J.npieces == 2) {
+            finish_pair<D>(pe, grp, J.wf, J.tile_index, J.piece, slot, o, m, ltot, lane, row_ok, J.seg_cu + t, head);
+        } else {
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
+                    part[(db * 4 + q4) * 64 + lane] = x;
+                }
+            finish_tile<D>(pe, grp, J.wf, J.tile_index, J.npieces, J.piece, slot, part, m, ltot, lane, row_ok, J.seg_cu + t, head);
+        }
         TETRI_MARK((first_job ? 0 : 12) + 6);
         return;
     }
@@ -871,6 +963,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
     if (!row_ok) return;
     const float inv = __builtin_amdgcn_rcpf(ltot);
+    uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t) * pe.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -924,6 +1017,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     __shared__ uint4 smem[4 * STAGE_U4];             // K and V of two stage buffers: K0 | K1 | V0 | V1
     __shared__ float Mstat[kSlots][2][32];
     __shared__ uint32_t peek[kSlots][64];            // where a look at a tile's arrival counter lands
+    __shared__ int old_stash[kSlots];                // what a wavefront's announcement of an earlier job's piece found
     __shared__ int4 seg_tab[64];                     // stream mode: (first row, rows, cached tokens) of every segment
     __shared__ AttnParams params;
     TETRI_MARK(0);
@@ -946,9 +1040,9 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int grp = xcd * p.gpx + (local - widx * p.gpx);
     const int G = p.stream_wgs;
     // the arrival counters of the next launch that divides tiles: all zero when this launch ends
-    if (G != 0)
+    if (G != 0 || p.helpers != 0)
         for (int i = abid * NT + threadIdx.x; i < p.n_counters; i += p.attn_grid * NT) p.counters_next[i] = 0;
-    if (grp >= p.groups || widx >= (G != 0 ? G : p.tiles)) return;
+    if (grp >= p.groups || widx >= (G != 0 ? G : (p.helpers != 0 ? p.tiles + p.helpers - 2 : p.tiles))) return;
     if (threadIdx.x == 0) params = p;                // from scalar registers: no memory read to wait for
 
     int tid = threadIdx.x;
@@ -961,16 +1055,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int kh = magic_div(grp, p.kv_magic);
     const int first_page = min(wave, p.max_blocks - 1), first_page_hi = min(wave + kSlots, p.max_blocks - 1);
 
-    WaveSrc ws;
-    ws.bt = p.bt;
-    ws.new_k = reinterpret_cast<const char *>(p.k_new);
-    ws.new_v = reinterpret_cast<const char *>(p.v_new);
-    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * (kPage * D * 2);
-    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
-    ws.v_delta = p.Hkv * (kPage * D * 2);
-    ws.stage_new_bytes = STAGE * (p.Hkv * D * 2);
-    ws.wave_new_bytes = 16 * (p.Hkv * D * 2);
-    ws.max_blocks = p.max_blocks;
+    const WaveSrc ws = make_wave_src<D, KS>(p, kh);    // for the first job's first loads; every job derives its own
 
     // ---- the workgroup's first job.  Lane l looks at segment s0 + l (64 at a time); it also fetches
     // what the owner of the job will need next (context length, the pages of the segment's first
@@ -988,11 +1073,36 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     // cost a second round trip to memory
     const bool row_in_lanes = G != 0 && S == 1 && p.max_blocks <= 128;
     int bt_lo = 0, bt_hi = 0;
+    // tile and tail modes: the workgroup's second tile (a helper's, or the bound's last tile), as found by the lookup;
+    // its job is made when its turn comes
+    SegInfo lg0 = {-1, 0, 0, 0};
+    int lw0 = -1, lt0 = -1, n_later = 0, tail_piece = 0;
+    bool later_whole = false;                        // the second tile is done whole, whatever its length
+    int first_want = -1, first_t0 = -1;              // the first one (its segment is in `seg`)
+    bool pages_fetched = true;                       // page / page_hi are those of the first job's stage 0
     if (G == 0) {
-        // tile mode: row tile `tile` of the chunk, late (long) tiles first.  Tiles never span two segments.
-        int tile = p.tiles - 1 - widx;
-        tile_index = tile;
-        int t0 = -1;
+        // Tile mode: row tile T - 1 - widx, late (long) tiles first.  Tail mode (helpers != 0): first the owners
+        // of the tiles but the last one of the host's bound (which is real only in chunks with ragged segments),
+        // each doing its tile's key range but for the tail, then the helpers, each doing the tails of two of
+        // those tiles.  The bound's last tile gets no workgroup of its own (it would start when the first compute
+        // unit becomes free and, though empty, end after everybody else): it is one more job, done whole, of
+        // the owner of tile 0, whose key range is the shortest.  Tiles never span two segments.
+        const int T = p.tiles, H = p.helpers;
+        int want0, want1 = -1;
+        int &piece = tail_piece;
+        if (H == 0) {
+            want0 = T - 1 - widx;
+        } else if (widx < T - 1) {
+            want0 = T - 2 - widx;
+            if (want0 == 0) { want1 = T - 1; later_whole = true; }
+        } else {
+            piece = 1;
+            want0 = T - 2 - 2 * (widx - (T - 1));
+            if (want0 >= 1) want1 = want0 - 1;
+        }
+        // one pass over the segments finds both
+        SegInfo g0 = {-1, 0, 0, 0}, g1 = g0;
+        int t00 = -1, t01 = -1, base = 0;
         for (int s0 = 0; s0 < S; s0 += 64) {
             const int idx = s0 + lane;
             const int a = idx < S ? p.cu[idx] : 0, b = idx < S ? p.cu[idx + 1] : 0;
@@ -1006,37 +1116,81 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 const int y = __shfl_up(incl, d, 64);
                 if (lane >= d) incl += y;
             }
-            const unsigned long long owner = __builtin_amdgcn_ballot_w64(tile >= incl - ntl && tile < incl);
-            if (owner != 0) {
-                const int o = __builtin_ctzll(owner);
-                seg.s = s0 + o;
-                t0 = (tile - __builtin_amdgcn_readlane(incl - ntl, o)) * BM;
-                seg.seg_cu = __builtin_amdgcn_readlane(a, o);
-                seg.n_s = __builtin_amdgcn_readlane(b - a, o);
-                seg.L = __builtin_amdgcn_readlane(ctx_len, o);
-                page = __builtin_amdgcn_readlane(pg, o);
-                page_hi = __builtin_amdgcn_readlane(pg_hi, o);
-                break;
-            }
-            tile -= __builtin_amdgcn_readlane(incl, 63);
+            auto find = [&](int want, SegInfo &g, int &t0, bool pages) __attribute__((always_inline)) {
+                const int rel = want - base;
+                const unsigned long long owner = __builtin_amdgcn_ballot_w64(t0 < 0 && want >= 0 && rel >= incl - ntl && rel < incl);
+                if (owner != 0) {
+                    const int o = __builtin_ctzll(owner);
+                    g.s = s0 + o;
+                    t0 = (rel - __builtin_amdgcn_readlane(incl - ntl, o)) * BM;
+                    g.seg_cu = __builtin_amdgcn_readlane(a, o);
+                    g.n_s = __builtin_amdgcn_readlane(b - a, o);
+                    g.L = __builtin_amdgcn_readlane(ctx_len, o);
+                    if (pages) {
+                        page = __builtin_amdgcn_readlane(pg, o);
+                        page_hi = __builtin_amdgcn_readlane(pg_hi, o);
+                    }
+                }
+            };
+            find(want0, g0, t00, true);
+            find(want1, g1, t01, false);
+            base += __builtin_amdgcn_readlane(incl, 63);
         }
-        if (t0 < 0) {
-            // past the last segment's tiles: the padding rows [cu[S], C), one 32-row block per wavefront slot
-            if (kq == 0) {
+        TETRI_MARK(8);
+        // a wanted tile past the last segment's tiles: the padding rows [cu[S], C), one 32-row block per wavefront slot
+        auto pad_tile = [&](int want, int t0) __attribute__((always_inline)) {
+            if (want >= 0 && t0 < 0 && piece == 0 && kq == 0) {
                 const int hh = slot & (p.hpw - 1), rbk = slot >> p.hpw_shift;
-                const int r = p.cu[S] + tile * BM + 32 * rbk + (lane & 31);
+                const int r = p.cu[S] + (want - base) * BM + 32 * rbk + (lane & 31);
                 if (r < p.C) {
                     uint4 *o = reinterpret_cast<uint4 *>(p.out + ((size_t)r * p.Hq + grp * p.hpw + hh) * D);
                     for (int c = lane >> 5; c < D / 8; c += 2) o[c] = make_uint4(0, 0, 0, 0);
                 }
             }
-            return;
+        };
+        pad_tile(want0, t00);
+        pad_tile(want1, t01);
+        auto tail_ok = [&](int want, const SegInfo &g, int t0) __attribute__((always_inline)) -> bool {
+            // whether this workgroup has a job on that tile: it exists, and a helper's tile hands a tail over
+            if (want < 0 || t0 < 0) return false;
+            if (piece == 0) return true;
+            const int n_new = min(g.n_s, t0 + BM);
+            const int n_all = (g.L + STAGE - 1) / STAGE + (n_new + STAGE - 1) / STAGE;
+            return n_all >= p.split_min && ((max(n_all - p.split_bias, 0) * p.tail_q8 + 128) >> 8) != 0;
+        };
+        const bool v0 = tail_ok(want0, g0, t00), v1 = tail_ok(want1, g1, t01);
+        if (!v0 && !v1) return;
+        // the first valid one becomes J, a second one waits as (tile, segment, first row)
+        pages_fetched = v0;
+        seg.s = v0 ? g0.s : g1.s;
+        seg.seg_cu = v0 ? g0.seg_cu : g1.seg_cu;
+        seg.n_s = v0 ? g0.n_s : g1.n_s;
+        seg.L = v0 ? g0.L : g1.L;
+        first_want = v0 ? want0 : want1;
+        first_t0 = v0 ? t00 : t01;
+        n_later = (int)(v0 && v1);
+        lg0 = g1; lw0 = want1; lt0 = t01;
+    }
+    // The piece of a tile this workgroup does in tile and tail mode: all of it, or with a tail handed over (key ranges
+    // of at least split_min stages) everything but the tail / the tail.  A helper has about split_bias stages' worth of
+    // extra work (a second tile's prologue, handing its first result over): owners and helpers finish together when
+    // each tile hands over the share tail_q8 / 256 of what exceeds that.
+    // (pp: the launch parameters, from the kernel arguments for a workgroup's first jobs, from their copy in LDS later:
+    // kept in scalar registers across the jobs they would push other values out to memory)
+    auto make_piece = [&](const AttnParams &pp, int want, const SegInfo &g, int t0, bool whole, Job &X) __attribute__((always_inline)) {
+        const int H = whole ? 0 : pp.helpers, piece = tail_piece;
+        {
+            X.seg_cu = g.seg_cu; X.n_s = g.n_s; X.t0 = t0; X.tile_index = want;
+            X.src = make_src<D, KS>(pp, kh, g, t0);
+            const int n_all = X.src.n_ctx_tiles + (X.src.n_new + STAGE - 1) / STAGE;
+            const int n_tail = (H != 0 && n_all >= pp.split_min) ? (max(n_all - pp.split_bias, 0) * pp.tail_q8 + 128) >> 8 : 0;
+            X.it_begin = piece == 0 ? 0 : n_all - n_tail;
+            X.it_end = piece == 0 ? n_all - n_tail : n_all;
+            X.piece = piece; X.npieces = n_tail != 0 ? 2 : 1; X.wf = 0;
         }
-        J.seg_cu = seg.seg_cu; J.n_s = seg.n_s; J.t0 = t0; J.tile_index = tile_index;
-        J.src = make_src<D, KS>(p, kh, seg, t0);
-        J.it_begin = 0;
-        J.it_end = J.src.n_ctx_tiles + (J.src.n_new + STAGE - 1) / STAGE;
-        J.piece = 0; J.npieces = 1; J.wf = 0;
+    };
+    if (G == 0) {
+        make_piece(p, first_want, seg, first_t0, false, J);
     } else {
         // stream mode (S <= 64): every workgroup of the group works out the same division
         const int a = lane < S ? p.cu[lane] : 0, b = lane < S ? p.cu[lane + 1] : 0;
@@ -1096,9 +1250,9 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     }
 
     // a job of stream mode from the cursor (seg, j, tile_lin, tile_index, pos); moves the cursor behind it
-    auto stream_job = [&](Job &X) __attribute__((always_inline)) {
+    auto stream_job = [&](const AttnParams &pp, Job &X) __attribute__((always_inline)) {
         X.seg_cu = seg.seg_cu; X.n_s = seg.n_s; X.t0 = j << bm_shift; X.tile_index = tile_index;
-        X.src = make_src<D, KS>(p, kh, seg, X.t0);
+        X.src = make_src<D, KS>(pp, kh, seg, X.t0);
         const int n_all = X.src.n_ctx_tiles + (X.src.n_new + STAGE - 1) / STAGE;
         const int tile_end = tile_lin + n_all;
         X.it_begin = pos - tile_lin;
@@ -1124,7 +1278,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             }
         }
     };
-    if (G != 0) stream_job(J);
+    if (G != 0) stream_job(p, J);
     TETRI_MARK(9);
 
     // ---- the first job's first stage and its Q rows.  The wavefronts of key part 0 reach this point
@@ -1145,7 +1299,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         };
         constexpr int PPS = kBNW * KS / kPage;           // pages per stage
         if (kq == 0) {
-            if (J.it_begin != 0) {                       // the lookup fetched the pages of stage 0
+            if (J.it_begin != 0 || !pages_fetched) {     // the lookup fetched the pages of stage 0 of its first tile
                 page = row_entry(J.it_begin * PPS + wave);
                 page_hi = row_entry(J.it_begin * PPS + wave + kSlots);
             }
@@ -1166,10 +1320,22 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     Handover ho;
     int guard = p.tiles + 2;                         // a workgroup never has more jobs than the chunk has tiles: malformed metadata cannot keep it here
     for (bool first = true;; first = false) {
-        const bool more = G != 0 && pos < b1 && --guard > 0;
+        const bool more = G != 0 ? (pos < b1 && --guard > 0) : n_later > 0;
         Job N = J;
-        if (more) stream_job(N);
-        tile_job<D, KS>(p, first, &params, smem, Mstat, peek, grp, J, more, N, ws, cy, ho);
+        if (more) {
+            AttnParams pj = p;                       // before the first job's first barrier the copy in LDS may be incomplete
+            if (!first) {
+                asm volatile("" ::: "memory");
+                pj = read_params(&params);
+            }
+            if (G != 0) {
+                stream_job(pj, N);
+            } else {
+                make_piece(pj, lw0, lg0, lt0, later_whole, N);
+                --n_later;
+            }
+        }
+        tile_job<D, KS>(p, first, &params, smem, Mstat, peek, old_stash, grp, kh, J, more, N, cy, ho);
         if (!more) break;
         J = N;
     }
@@ -1179,20 +1345,14 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         constexpr int DBLK = D / 32;
         asm volatile("" ::: "memory");
         const AttnParams pd = read_params(&params);
-        if (!ho.announced) {                         // not reached: every job has a stage, whose barrier announces
-            wait_vm<0>();
-            if (lane == 0) ho.old = atomicAdd(pd.counters + ho.unit, 1);
-        }
-        if (__builtin_amdgcn_readfirstlane(ho.old) == ho.npieces - 1) {
-            f32x16 o[DBLK];
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+        // (derived anew from the thread id: kept from the start of the kernel they would occupy registers across all jobs)
+        int tid_end = threadIdx.x;
+        asm volatile("" : "+v"(tid_end));
+        const int lane = tid_end & 63, slot = __builtin_amdgcn_readfirstlane(tid_end >> 6) % kSlots;
+        if (__builtin_amdgcn_readfirstlane(old_stash[slot]) == ho.npieces - 1) {
             const int head = grp * pd.hpw + (slot & (pd.hpw - 1));
             const int t = ho.t0 + 32 * (slot >> pd.hpw_shift) + (lane & 31);
-            finish_tile<D>(pd, grp, ho.wf, ho.npieces, -1, slot, o, 0.f, 0.f, lane, t < ho.n_s,
-                           pd.out + ((size_t)(ho.seg_cu + t) * pd.Hq + head) * D);
+            finish_tile<D>(pd, grp, ho.wf, ho.tile_index, ho.npieces, -1, slot, nullptr, 0.f, 0.f, lane, t < ho.n_s, ho.seg_cu + t, head);
         }
     }
     TETRI_MARK(7);

@@ -123,6 +123,21 @@ tetri_status tetri_set_option(tetri_ctx *ctx, const char *key, int32_t value)
         ctx->split_keys = value;
         return TETRI_OK;
     }
+    if (std::strcmp(key, "split_min_stages") == 0) {
+        if (value < 2) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_min_stages=%d (at least 2)", value);
+        ctx->split_min_stages = value;
+        return TETRI_OK;
+    }
+    if (std::strcmp(key, "split_bias_stages") == 0) {
+        if (value < 0) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_bias_stages=%d (not negative)", value);
+        ctx->split_bias_stages = value;
+        return TETRI_OK;
+    }
+    if (std::strcmp(key, "split_share_q8") == 0) {
+        if (value < 1 || value > 128) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: split_share_q8=%d (1..128)", value);
+        ctx->split_share_q8 = value;
+        return TETRI_OK;
+    }
     if (std::strcmp(key, "stream_wgs") == 0) {
         if (value < 0 || value > 255) return fail(ctx, TETRI_ERR_INVALID_ARG, "tetri_set_option: stream_wgs=%d (0..255)", value);
         ctx->stream_wgs = value;
@@ -394,24 +409,42 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     if (h->attn_variant == 0 && h->stream_wgs == 0 && (int64_t)(p.C / (32 * p.rb)) * groups >= 2 * (int64_t)cus) key_parts = 1;
     p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
     p.gpx = (groups + 7) / 8;
-    // Stream mode: a launch with fewer than two row tiles per compute unit gives every head group G workgroups
-    // that share the stages of all its tiles evenly (one workgroup per compute unit, a few units left to the
-    // fused append).  The division is worked out on the device from the segment lengths; the host only has to
-    // know that its numbers fit: at most 64 segments (one lane each), positions and their products with G in 31
-    // bits, scratch memory and arrival counters for every (workgroup, slot) and (tile, slot).
+    // How the work of a head group is handed out (see the kernel):
+    //  - tail mode: a launch whose row tiles would occupy at most two thirds of the compute units gets one more
+    //    workgroup per two tiles, which takes the tails of their key ranges; all tiles of a head start together and
+    //    walk the keys side by side, so K and V come out of L2 for all but the first of them;
+    //  - stream mode: a launch with more tiles than that but fewer than two per compute unit gives every head
+    //    group G workgroups that share the stages of all its tiles evenly (measured: better than a second, mostly
+    //    empty round of workgroups, worse than tail mode where that applies: workgroups of a head then read
+    //    different parts of K and V at any one time);
+    //  - tile mode: one workgroup per row tile.
+    // The divisions are worked out on the device from the segment lengths; the host only has to know that
+    // the numbers fit: scratch memory and arrival counters for every (tile, slot) resp. (workgroup, slot), and for
+    // stream mode at most 64 segments (one lane each) and positions times G in 31 bits.
     int G = 0;
-    if (h->stream_wgs > 0) G = h->stream_wgs;
-    else if (h->split_keys && (int64_t)p.tiles * groups < 2 * (int64_t)cus) G = std::min(255, (cus - (kv_pages_w ? 8 : 0)) / groups);
+    p.helpers = 0;
+    const bool counters_fit = (int64_t)groups * p.tiles * 4 <= h->n_counters;
+    if (h->stream_wgs > 0) {
+        G = h->stream_wgs;
+    } else if (h->split_keys) {
+        const int helpers = p.tiles / 2 + 1;
+        // (the last tile of the bound and its helper exist only in chunks with ragged segments and are not counted)
+        if (p.tiles >= 2 && (int64_t)(p.tiles - 1 + helpers - 1) * groups <= cus && (size_t)p.tiles * groups * 4 <= h->scratch_units)
+            p.helpers = helpers;
+        else if ((int64_t)p.tiles * groups < 2 * (int64_t)cus)
+            G = std::min(255, (cus - (kv_pages_w ? 8 : 0)) / groups);
+    }
     const int stage = 64 * key_parts;
     const int64_t stage_bound = (int64_t)p.tiles * (((int64_t)p.max_blocks * 16 + p.C) / stage + 2);
-    if (G > 0 && (p.S > 64 || stage_bound * (G + 1) >= 0x7fffffffll || (size_t)groups * G * 4 > h->scratch_units ||
-                  (int64_t)groups * p.tiles * 4 > h->n_counters))
+    if (G > 0 && (p.S > 64 || stage_bound * (G + 1) >= 0x7fffffffll || (size_t)groups * G * 4 > h->scratch_units || !counters_fit))
         G = 0;
+    if (!counters_fit) p.helpers = 0;
+    const bool shares = G > 0 || p.helpers > 0;         // the launch uses the handle's scratch memory and counters
     hipStream_t hs = static_cast<hipStream_t>(stream);
     // (a stream that is being captured into a graph takes no event queries or records: the graph orders its nodes)
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    const bool capturing = G > 0 && (hipStreamIsCapturing(hs, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone);
-    if (G > 0) {
+    const bool capturing = shares && (hipStreamIsCapturing(hs, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone);
+    if (shares) {
         // the scratch memory lives on the device the handle was created on
         int dev = -1;
         if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
@@ -424,13 +457,14 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
                         "pending; launches on one handle must not overlap (use one handle per stream)", fn);
     }
     p.stream_wgs = G;
-    p.attn_grid = 8 * p.gpx * (G > 0 ? G : p.tiles);
+    // (in tail mode the bound's last tile and its helper are extra jobs of existing workgroups)
+    p.attn_grid = 8 * p.gpx * (G > 0 ? G : (p.helpers > 0 ? p.tiles + p.helpers - 2 : p.tiles));
     p.attn_first = p.attn_grid;
     // fused append: a few dozen workgroups, each copying every 64th row of the chunk
     // (every eight-wavefront workgroup of this kernel occupies a whole CU: in stream mode only the CUs the
     // attention workgroups leave free take append workgroups right away)
     int append_wgs = 64;
-    if (G > 0) {
+    if (shares) {
         const int idle = cus - p.attn_first;
         append_wgs = idle >= 8 ? (idle < 64 ? idle / 8 * 8 : 64) : 8;
     }
@@ -442,6 +476,9 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     p.rb_shift = log2i(p.rb);
     p.groups = groups;
     p.gpx_magic = magic((uint32_t)p.gpx);
+    p.tail_q8 = h->split_share_q8;
+    p.split_min = h->split_min_stages;
+    p.split_bias = h->split_bias_stages;
     p.scratch = h->scratch;
     p.n_counters = h->n_counters;
     p.counters = h->counters + (size_t)h->counter_set * h->n_counters;
@@ -451,7 +488,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
     hipError_t e = tetri_launch_attn(h, p, key_parts, hs);
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
-    if (G > 0) {
+    if (shares) {
         h->counter_set = 1 - h->counter_set;
         if (!capturing) {
             h->last_divide_stream = hs;

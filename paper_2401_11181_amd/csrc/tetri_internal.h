@@ -12,6 +12,9 @@ struct tetri_ctx {
     int attn_variant = 0;   // 0 = library's choice, 1 / 2 = shared-tile kernel with 1 / 2 key parts
     int split_keys = 1;     // 1 = launches with fewer than two row tiles per CU divide the stages of every head group evenly over the CUs
     int stream_wgs = 0;     // workgroups per head group of such a launch (0: as many as the device has CUs for); > 0 forces the mode
+    int split_min_stages = 8;   // tail mode: the shortest key range that hands its tail to a helper workgroup
+    int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
+    int split_share_q8 = 85;    // the share of the remaining stages a tile hands over, in 1/256 (a third)
     int decode_parts = 0;       // key parts per (request, kv head) of the decode kernel (0: the library chooses)
     int transfer_slabs = 0;     // (K / V, head) slabs per workgroup of the export / import kernels (0: the library chooses)
     int device = 0;         // the device the handle was created on; its scratch memory lives there
@@ -41,7 +44,11 @@ struct AttnParams {
     int32_t rb;           // 32-row blocks handled by one workgroup
     int32_t hpw_shift, rb_shift;   // log2 of the two
     int32_t groups;       // Hq / hpw: head groups, one workgroup column each
-    int32_t stream_wgs;   // workgroups per head group that share its stages evenly (0: one workgroup per row tile)
+    int32_t stream_wgs;   // workgroups per head group that share its stages evenly (0: one workgroup per row tile ...)
+    int32_t helpers;      // ... plus, per head group, this many that take the tails of two tiles' key ranges each (0: none)
+    int32_t tail_q8;      // the share of a tile's stages that goes to its helper, in 1/256
+    int32_t split_min;    // only key ranges of at least this many stages hand a tail over
+    int32_t split_bias;   // stages not counted when a key range's tail is measured
     int32_t n_counters;   // size of a set of arrival counters
     int32_t gpx;          // head groups per XCD
     uint32_t gpx_magic;   // ceil(2^32 / gpx), 0 for 1

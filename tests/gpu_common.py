@@ -23,17 +23,21 @@ def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_c
     sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                           w.num_pages, tables, device=DEV, page_size=w.page_size)
     # variants 0 / 1 / 2: the library's choice / 4-wavefront / 8-wavefront workgroups, each with the library's
-    # choice of how the work is handed out (small launches: the stages of a head group divided evenly over as many
-    # workgroups as the device has compute units for, i.e. many pieces per tile); 10 / 11: 8- / 4-wavefront
-    # workgroups with 5 workgroups per head group; 13: with 2 (every workgroup runs many jobs); 12: one workgroup per
-    # row tile, never divided
-    sess.handle.tetri_set_option("attn_variant", variant if variant < 10 else (1 if variant == 11 else 2))
-    if variant in (10, 11):
-        sess.handle.tetri_set_option("stream_wgs", 5)
+    # choice of how the work is handed out; 10 / 11: 8- / 4-wavefront workgroups, tail mode with every key range of
+    # two or more stages handing its last third to a helper workgroup (the library itself only does so for long
+    # ones); 13: half of it (helpers settle their first tile late); 12: one workgroup per row tile, nothing
+    # divided; 14 / 15: stream mode with 5 workgroups per head group, 8 / 4 wavefronts; 16: with 2 (every workgroup
+    # runs many jobs); 17: with 200 (a stage per workgroup: as many pieces per tile as it has stages)
+    sess.handle.tetri_set_option("attn_variant", variant if variant < 10 else (1 if variant in (11, 15) else 2))
+    if variant in (10, 11, 13):
+        sess.handle.tetri_set_option("split_min_stages", 2)
+        sess.handle.tetri_set_option("split_bias_stages", 0)
     if variant == 13:
-        sess.handle.tetri_set_option("stream_wgs", 2)
+        sess.handle.tetri_set_option("split_share_q8", 128)
     if variant == 12:
         sess.handle.tetri_set_option("split_keys", 0)
+    if variant in (14, 15, 16, 17):
+        sess.handle.tetri_set_option("stream_wgs", {14: 5, 15: 5, 16: 2, 17: 200}[variant])
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
     dq = [t.to(DEV) for t in qs]
     dk = [t.to(DEV) for t in ks]

@@ -13,14 +13,14 @@ import gpu_common as gc
 
 pytestmark = pytest.mark.gpu
 
-# attention kernel variants: 0 = library's choice, 1 / 2 = 4- / 8-wavefront workgroups (small launches divide the
-# stages of each head group evenly over many workgroups, whose partial results of shared tiles are merged);
-# 10 / 11 = 8- / 4-wavefront workgroups with five workgroups per head group, 13 = with two (many jobs per
-# workgroup), 12 = one workgroup per row tile, nothing divided.  Every variant must meet the same bar.
-VARIANTS = [0, 1, 2, 10, 11, 12, 13]
+# attention kernel variants: 0 = library's choice, 1 / 2 = 4- / 8-wavefront workgroups; 10 / 11 = tail mode (helper
+# workgroups take the last third of every key range of two or more stages) with 8 / 4 wavefronts, 13 = half of it;
+# 12 = one workgroup per row tile, nothing divided; 14 / 15 = stream mode (the stages of a head group divided evenly
+# over five workgroups) with 8 / 4 wavefronts, 16 = over two, 17 = over two hundred.  Every variant must meet the same bar.
+VARIANTS = [0, 1, 2, 10, 11, 12, 13, 14, 15, 16, 17]
 
 
-@pytest.fixture(params=VARIANTS, ids=["auto", "wave4", "wave8", "stream5", "stream5-wave4", "whole", "stream2"])
+@pytest.fixture(params=VARIANTS, ids=["auto", "wave4", "wave8", "tails", "tails-wave4", "whole", "tails-half", "stream5", "stream5-wave4", "stream2", "stream200"])
 def variant(request):
     return request.param
 

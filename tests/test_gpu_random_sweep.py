@@ -41,7 +41,7 @@ def test_random_workload(oracle, seed):
     w = draw(seed)
     print(w.prompt_lens, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim, round(w.scale, 4), flush=True)
     qs, ks, vs, tables = gc.workload_tensors(w)
-    variant = [0, 10, 11, 13][seed % 4]
+    variant = [0, 10, 11, 13, 14, 15, 16, 17][seed % 8]
     outs, pool, sess, _ = gc.gpu_prefill(w, qs, ks, vs, tables, fused=(seed % 2 == 0), variant=variant)
     ref, _, _ = gc.oracle_prefill(oracle, w, qs, ks, vs, tables)
     gc.compare(outs, ref, label=w.name)

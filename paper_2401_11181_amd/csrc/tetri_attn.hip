@@ -608,13 +608,14 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         __syncthreads();
         return stage_blocks(it);
     };
+    const int32_t *bt_row = ws.bt + src.bt_off;      // the job's block-table row
     auto next_stage_loads = [&](int it, int nb, bool pv_before) {
         if (it + 1 < n_stages) {
             const bool full = describe_stage_loads<D, KS>(src, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
             if (full && pv_before && nb != 0 && load_point != 0) pend = true;
             else issue_stage_loads<D, KS>(sl, full, lane);
         }
-        page = load_stage_page<KS>(ws.bt + src.bt_off, ws.max_blocks, it + 2, wave);
+        page = load_stage_page<KS>(bt_row, ws.max_blocks, it + 2, wave);
     };
     auto qk = [&](const bf16x8 (&kf)[KSTEPS]) -> f32x16 {
         f32x16 sacc;
@@ -1133,7 +1134,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 }
             };
             find(want0, g0, t00, true);
-            find(want1, g1, t01, false);
+            if (want1 >= 0) find(want1, g1, t01, false);
             base += __builtin_amdgcn_readlane(incl, 63);
         }
         TETRI_MARK(8);
@@ -1149,7 +1150,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             }
         };
         pad_tile(want0, t00);
-        pad_tile(want1, t01);
+        if (want1 >= 0) pad_tile(want1, t01);
         auto tail_ok = [&](int want, const SegInfo &g, int t0) __attribute__((always_inline)) -> bool {
             // whether this workgroup has a job on that tile: it exists, and a helper's tile hands a tail over
             if (want < 0 || t0 < 0) return false;
@@ -1158,7 +1159,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             const int n_all = (g.L + STAGE - 1) / STAGE + (n_new + STAGE - 1) / STAGE;
             return n_all >= p.split_min && ((max(n_all - p.split_bias, 0) * p.tail_q8 + 128) >> 8) != 0;
         };
-        const bool v0 = tail_ok(want0, g0, t00), v1 = tail_ok(want1, g1, t01);
+        const bool v0 = tail_ok(want0, g0, t00), v1 = want1 >= 0 && tail_ok(want1, g1, t01);
         if (!v0 && !v1) return;
         // the first valid one becomes J, a second one waits as (tile, segment, first row)
         pages_fetched = v0;

@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the chunked-prefill hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload opt13b] [--mode graph|eager]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload opt13b] [--mode eager|graph]
 
-One "step" is one pass of the whole hot path over one scheduled batch of synthetic input:
-host chunk packing + per-chunk metadata, one metadata upload, then for every chunk in order one
-attention launch and one KV-append launch (TetriInfer Sec. 3.3.3: prefill one ChunkSize chunk at
-a time).  Q/K/V of every chunk and the page pool are resident in HBM before the timed region.
-Prints ONE JSON line.  `value` = algorithmic attention flops of a step / step time.
+One "step" is one pass of the whole hot path over one scheduled batch of synthetic input: host chunk
+packing + per-chunk metadata, one metadata upload, then for every chunk in order ONE launch that does the
+chunk's attention and its KV append (TetriInfer Sec. 3.3.3: prefill one ChunkSize chunk at a time;
+--two-launches runs the two kernels separately).  Q/K/V of every chunk and the page pool are resident in
+HBM before the timed region.  Prints ONE JSON line.
 
-Beside the contract's fields the line carries stand-alone measurements taken after the timed region (HIP
-events around graph-replayed groups of launches): `per_chunk`, `append`, `kv_transfer` (request-level KV
-export / import of the batch, Sec. 3.3.4) and `decode` (one decode iteration of 64 requests x 2048 cached
-tokens on the same head shape).  Other modes: --policy / --sched-batch (prefill scheduler, Sec. 3.3.2),
---chunk-size / --prompt-len and --layer-sweep (the saturation experiment of Sec. 2.2), --export (KV export
-inside the step at request or chunk granularity).
+`value` = algorithmic attention flops of a step / step time with a COLD cache: consecutive steps rotate over
+independent copies of every buffer (inputs, output, page pool), so that more than twice the 256 MB last-level
+cache is touched before a buffer comes round again.  `warm_cache` is the same step on one set of buffers, back
+to back.  `roofline` is the attention kernel alone, its launch durations measured with HIP events (on the
+launch stream) around graph-replayed groups of launches that rotate over the same buffer sets.
+
+Beside the contract's fields the line carries stand-alone measurements taken after the timed region:
+`per_chunk`, `roofline.per_chunk_bound_frac` (each chunk against the roofline that binds it:
+max(flops / MFMA peak, bytes / HBM peak) / duration), `append`, `kv_transfer` (request-level KV export /
+import, Sec. 3.3.4), `decode` (one decode iteration of 64 requests x 2048 cached tokens on the same head
+shape) and `cpu_baseline` (the CPU oracle on this machine's host cores over a bounded sample of the same
+workload).  Other modes: --policy / --sched-batch (prefill scheduler, Sec. 3.3.2), --chunk-size /
+--prompt-len, --sweep (the ChunkSize saturation experiment of Sec. 2.2 in one run), --layer-sweep (the same
+for a whole decoder layer), --export (KV export inside the step).
 """
 import argparse
 import dataclasses
@@ -28,9 +36,42 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# plain copy of known size (figures and commands: profiles/attn_tile_kernel_opt13b_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {("opt13b", "fused"): 76.5e6}
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled
+# by a plain copy of known size.  A profiled figure, not one of this run: (bytes, the summary that holds it).
+PROFILED_TRAFFIC = {("opt13b", "fused"): (76.5e6, "profiles/attn_tile_kernel_opt13b_hbm_traffic.md")}
+
+
+# ---- algorithmic work of a chunk: what the method must do (masked pairs and padding rows count zero)
+def chunk_pairs(segs):
+    """Unmasked (query, key) pairs per query head: sum over segments of n * ctx + n (n + 1) / 2."""
+    return sum(n * start + n * (n + 1) // 2 for _req, start, n in segs)
+
+
+def chunk_flops(segs, hq, d):
+    """QK^T and PV: 4 * D * Hq * pairs."""
+    return 4 * d * hq * chunk_pairs(segs)
+
+
+def chunk_attn_bytes(segs, hq, hkv, d, page=16):
+    """HBM bytes of one attention launch: Q in and out once, K and V once, the block table."""
+    n = sum(x[2] for x in segs)
+    kv = sum((start + ln) * hkv * d * 2 * 2 for _r, start, ln in segs)
+    bt = sum(-(-start // page) * 4 for _r, start, _ln in segs)
+    return 2 * n * hq * d * 2 + kv + bt
+
+
+def chunk_append_bytes(segs, hkv, d):
+    """The new K and V rows read once more and written once."""
+    n = sum(x[2] for x in segs)
+    return 2 * 2 * n * hkv * d * 2
+
+
+def set_options(pipe, args):
+    if args.variant is not None:
+        pipe.handle.tetri_set_option("attn_variant", args.variant)
+    for kv in args.opt:
+        key, value = kv.split("=")
+        pipe.handle.tetri_set_option(key, int(value))
 
 
 def layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev):
@@ -72,7 +113,7 @@ def layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev):
         attn_ms = timed(lambda: pipe.launch_fused(0))
         x = [(torch.randn(C, kdim, device=dev) * 0.02).to(torch.bfloat16) for kdim, _n in shapes]
         gemm_ms = sum(timed(lambda i=i: torch.matmul(x[i], weights[i])) for i in range(4))
-        attn_flops = pipe.flops(0)
+        attn_flops = chunk_flops(pipe.chunk_segments(0), heads, d)
         gemm_flops = sum(2.0 * C * kdim * n for kdim, n in shapes)
         rows.append({"C": C, "attn_ms": round(attn_ms, 5), "gemm_ms": round(gemm_ms, 5),
                      "layer_ms": round(attn_ms + gemm_ms, 5),
@@ -83,6 +124,54 @@ def layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev):
     print(json.dumps({"metric": "layer_prefill_saturation_sweep", "unit": "TFLOP/s", "data": "synthetic",
                       "config": {"workload": "one OPT-13B-shaped decoder layer (hidden 5120, 40x128 heads), one prompt of C tokens, "
                                              "empty cache, bf16; attention = this library, projections = library GEMMs"},
+                      "rows": rows}))
+    return 0
+
+
+def chunk_sweep(torch, np, synth, tetri, PrefillPipeline, dev, args):
+    """The saturation experiment of Sec. 2.2 (the token count per iteration beyond which prefill throughput stays
+    flat) for the attention of one prompt of --prompt-len tokens (default 8192) with the workload's head shape: one
+    row per ChunkSize, the whole step (pack, metadata, upload, every chunk's fused launch) timed on one set of
+    buffers.  One JSON line."""
+    base = synth.workload(args.workload)
+    plen = args.prompt_len or 8192
+    rows = []
+    for C in (128, 256, 512, 1024, 2048, 4096, 8192):
+        if C > plen:
+            break
+        w = dataclasses.replace(base, prompt_lens=[plen], order=[0], chunk_size=C, num_pages=-(-plen // base.page_size) + 64)
+        pipe = PrefillPipeline(w.prompt_lens, w.order, C, w.num_q_heads, w.num_kv_heads, w.head_dim, w.num_pages,
+                               synth.place_pages(w), w.scale, device=dev, page_size=w.page_size)
+        set_options(pipe, args)
+        nC = pipe.n_chunks
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        q = (torch.randn((nC, C, w.num_q_heads, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        k = (torch.randn((nC, C, w.num_kv_heads, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        v = (torch.randn((nC, C, w.num_kv_heads, w.head_dim), device=dev, generator=gen) * w.std).to(torch.bfloat16)
+        out = torch.zeros_like(q)
+        pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=dev)
+        pipe.bind(q, k, v, pool, out)
+        flops = sum(chunk_flops(pipe.chunk_segments(c), w.num_q_heads, w.head_dim) for c in range(nC))
+        for _ in range(10):
+            pipe.step()
+        torch.cuda.synchronize()
+        steps = max(10, min(100, args.steps))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pipe.step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        tf = flops / (ms * 1e-3) / 1e12
+        rows.append({"chunk_size": C, "chunks": nC, "steps": steps, "ms_per_step": round(ms, 5), "ms_per_chunk": round(ms / nC, 5),
+                     "tflops": round(tf, 1), "frac_of_mfma_peak": round(tf / PEAK_BF16_MFMA_TFLOPS, 4),
+                     "tokens_per_ms": round(plen / ms, 1)})
+        del pipe, pool, q, k, v, out
+    print(json.dumps({"metric": "chunk_size_saturation_sweep", "unit": "TFLOP/s", "data": "synthetic", "dtype": "bf16", "n_gpus": 1,
+                      "config": {"workload": "%s head shape (%dx%d query heads, %d kv heads, page size %d): one prompt of %d tokens, "
+                                             "whole step per ChunkSize, one set of buffers, seed %d" % (
+                                                 base.name, base.num_q_heads, base.head_dim, base.num_kv_heads, base.page_size, plen,
+                                                 base.seed)},
                       "rows": rows}))
     return 0
 
@@ -101,7 +190,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="attention kernel variant (measurement only)")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
-                    help="tetri_set_option on the benchmark's handle (measurement only), e.g. --opt split_keys=0")
+                    help="tetri_set_option on the benchmark's handles (measurement only), e.g. --opt split_keys=0")
+    ap.add_argument("--buffer-sets", type=int, default=0,
+                    help="independent copies of every buffer that the steps rotate over (0: enough to touch more than "
+                         "twice the last-level cache between repeats; 1: one set, a warm cache)")
     ap.add_argument("--policy", default=None, choices=["fcfs", "sjf", "ljf"],
                     help="order the workload's requests with tetri_schedule (Sec. 3.3.2) before packing")
     ap.add_argument("--sched-batch", type=int, default=0, help="PrefillSchedBatch: requests per sorted group (0: all)")
@@ -112,7 +204,10 @@ def main():
                     help="instead of the benchmark: the paper's saturation experiment (Sec. 2.2) for one 13B-shaped "
                          "decoder layer: this library's attention of a C-token prompt plus the layer's four projections "
                          "as plain library GEMMs, for C = 128 .. 8192")
-    ap.add_argument("--chunk-size", type=int, default=None, help="ChunkSize override (the saturation sweep of Sec. 2.2)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark: the ChunkSize saturation sweep (Sec. 2.2) of one prompt of --prompt-len "
+                         "tokens (default 8192) for ChunkSize 128 .. 8192; one JSON line with a row per ChunkSize")
+    ap.add_argument("--chunk-size", type=int, default=None, help="ChunkSize override")
     ap.add_argument("--prompt-len", type=int, default=None, help="replace the workload's prompts by one prompt of this length")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -133,6 +228,8 @@ def main():
 
     if args.layer_sweep:
         return layer_sweep(torch, np, synth, tetri, PrefillPipeline, dev)
+    if args.sweep:
+        return chunk_sweep(torch, np, synth, tetri, PrefillPipeline, dev, args)
     w = synth.workload(args.workload)
     if args.prompt_len is not None:
         w = dataclasses.replace(w, name=w.name + "-len%d" % args.prompt_len, prompt_lens=[args.prompt_len], order=[0],
@@ -144,15 +241,18 @@ def main():
                                      args.sched_batch)
         w = dataclasses.replace(w, name="%s-%s%d" % (w.name, args.policy, args.sched_batch), order=[int(x) for x in order])
     tables = synth.place_pages(w)
-    pipe = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
-                           w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
-                           use_graph=(args.mode == "graph"), fused=not args.two_launches, export=args.export)
-    if args.variant is not None:
-        pipe.handle.tetri_set_option("attn_variant", args.variant)
-    for kv in args.opt:
-        key, value = kv.split("=")
-        pipe.handle.tetri_set_option(key, int(value))
+    fused = not args.two_launches
+
+    def new_pipe(export=None):
+        pp = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                             w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
+                             use_graph=(args.mode == "graph"), fused=fused, export=export)
+        set_options(pp, args)
+        return pp
+
+    pipe = new_pipe(args.export)
     nC, C = pipe.n_chunks, w.chunk_size
+    segs_of = [pipe.chunk_segments(c) for c in range(nC)]
 
     # inputs: what the QKV projection of each chunk would hand to this path, resident in HBM
     q = torch.zeros((nC, C, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
@@ -162,7 +262,7 @@ def main():
     host_reqs = {}
     for c in range(nC):
         at = 0
-        for req, start, n in pipe.chunk_segments(c):
+        for req, start, n in segs_of[c]:
             if req not in host_reqs:
                 host_reqs[req] = synth.request_qkv(w, req)
             rq, rk, rv = host_reqs[req]
@@ -175,43 +275,75 @@ def main():
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=dev)
     pipe.bind(q, k, v, pool, out)
 
-    flops = [pipe.flops(c) for c in range(nC)]
+    flops = [chunk_flops(s, w.num_q_heads, w.head_dim) for s in segs_of]
+    attn_bytes = [chunk_attn_bytes(s, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size) for s in segs_of]
+    app_bytes_of = [chunk_append_bytes(s, w.num_kv_heads, w.head_dim) for s in segs_of]
     total_flops = float(sum(flops))
+
+    # ---- cold cache: independent copies of every buffer (inputs, output, page pool) that consecutive steps rotate
+    # over, so that more than twice the 256 MB last-level cache is touched before a buffer comes round again.  In a
+    # model the chunk's own rows are warm (the projection just wrote them) and the cached context is cold: the
+    # truth lies between this figure and `warm_cache`.
+    per_set = (q.numel() + k.numel() + v.numel() + out.numel()) * 2 + sum(w.prompt_lens) * 2 * w.num_kv_heads * w.head_dim * 2
+    n_sets = args.buffer_sets or int(min(16, max(4, -(-(600 << 20) // per_set) + 1)))
+    if n_sets * (pool.numel() * 2 + per_set) > (96 << 30) or args.export:
+        n_sets = 1
+    sets, keep = [pipe], []
+    for _ in range(n_sets - 1):
+        pp = new_pipe()
+        bufs = (q.clone(), k.clone(), v.clone(), pool.clone(), torch.zeros_like(out))
+        pp.bind(*bufs)
+        keep.append(bufs)
+        sets.append(pp)
 
     # ---- settle: a fresh process shows one stall of tens of milliseconds a few hundred steps in
     # (clocks / runtime start-up); run past it, untimed, before the W warmup steps
     t_settle = time.perf_counter()
     n_settle = 0
     while time.perf_counter() - t_settle < args.settle:
-        for _ in range(20):
-            pipe.step()
+        for i in range(20):
+            sets[i % n_sets].step()
         torch.cuda.synchronize()
         n_settle += 20
     # ---- warmup, then exactly K timed steps bracketed by synchronisations
-    for _ in range(args.warmup):
-        pipe.step()
+    for i in range(args.warmup):
+        sets[i % n_sets].step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        pipe.step()
+    for i in range(args.steps):
+        sets[i % n_sets].step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel durations: HIP events (on the launch stream) around groups of R back-to-back
-    # launches of one chunk's kernel, replayed from a HIP graph so that the host launch path does not
-    # sit between the kernels; duration = group time / R
-    R, reps = 10, max(3, min(20, args.steps // 10))
-    stream = torch.cuda.current_stream()
+    # ---- the same on one set of buffers, back to back
+    warm = None
+    if n_sets > 1:
+        for _ in range(args.warmup):
+            pipe.step()
+        torch.cuda.synchronize()
+        tw0 = time.perf_counter()
+        for _ in range(args.steps):
+            pipe.step()
+        torch.cuda.synchronize()
+        warm_ms = (time.perf_counter() - tw0) * 1e3 / args.steps
+        warm = {"value": round(total_flops / (warm_ms * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "ms_per_step": round(warm_ms, 5),
+                "steps": args.steps}
 
+    # ---- per-kernel durations: HIP events (on the launch stream) around groups of R back-to-back launches of one
+    # chunk's kernel, replayed from a HIP graph so that the host launch path does not sit between the kernels;
+    # duration = group time / R.  The i-th launch of a group runs on buffer set i mod n_sets.
+    R = max(10, n_sets) // n_sets * n_sets
+    reps = max(3, min(20, args.steps // 10))
+    stream = torch.cuda.current_stream()
     spread = []                                     # (p10, p90) of every group_time call, in call order
 
     def group_time(launch):
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for _ in range(R):
-                launch()
+            for i in range(R):
+                launch(i)
         g.replay()
         torch.cuda.synchronize()
         times = []
@@ -226,19 +358,32 @@ def main():
         return float(np.median(times))
 
     torch.cuda.synchronize()
-    pipe.host_plan(0)
-    pipe.meta_dev.copy_(pipe.stage[0])
+    for pp in sets:
+        pp.host_plan(0)
+        pp.meta_dev.copy_(pp.stage[0])
     torch.cuda.synchronize()
-    main_launch = pipe.launch_attn if args.two_launches else pipe.launch_fused
-    attn_ms = np.array([group_time(lambda c=c: main_launch(c)) for c in range(min(nC, 64))])
-    app_ms = np.array([group_time(lambda c=c: pipe.launch_append(c)) for c in range(min(nC, 8))])
-    n_meas = len(attn_ms)
+    n_meas = min(nC, 64)
+    if fused:
+        attn_ms = np.array([group_time(lambda i, c=c: sets[i % n_sets].launch_fused(c)) for c in range(n_meas)])
+    else:
+        attn_ms = np.array([group_time(lambda i, c=c: sets[i % n_sets].launch_attn(c)) for c in range(n_meas)])
+    app_ms = np.array([group_time(lambda i, c=c: sets[i % n_sets].launch_append(c)) for c in range(min(nC, 8))])
+    warm_attn_ms = None
+    if n_sets > 1:
+        warm_attn_ms = [group_time(lambda i, c=c: (pipe.launch_fused(c) if fused else pipe.launch_attn(c))) for c in range(min(nC, 8))]
+        warm["attn_ms_median"] = [round(x, 5) for x in warm_attn_ms]
+        warm["note"] = "attn_ms_median: the first %d chunks' launches, each repeated on one set of buffers" % len(warm_attn_ms)
     attn_avg_ms = float(attn_ms.mean())                 # average duration of one attention launch
     attn_flops_per_launch = float(sum(flops[:n_meas])) / n_meas
     achieved_tflops = attn_flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
-    app_bytes = float(np.mean([pipe.append_bytes(c) for c in range(len(app_ms))]))
+    launch_bytes = [attn_bytes[c] + (app_bytes_of[c] if fused else 0) for c in range(n_meas)]
+    app_bytes = float(np.mean(app_bytes_of[:len(app_ms)]))
     app_avg_ms = float(app_ms.mean())
-    attn_med, app_med = attn_ms, app_ms
+    # each chunk against the roofline that binds it: the longer of its MFMA time and its HBM time, over its duration
+    mfma_s = [flops[c] / (PEAK_BF16_MFMA_TFLOPS * 1e12) for c in range(n_meas)]
+    hbm_s = [launch_bytes[c] / (PEAK_HBM_GBS * 1e9) for c in range(n_meas)]
+    bound_frac = [max(mfma_s[c], hbm_s[c]) / (float(attn_ms[c]) * 1e-3) for c in range(n_meas)]
+    traffic, traffic_src = PROFILED_TRAFFIC.get((w.name, "fused" if fused else "two"), (None, None))
 
     result = {
         "metric": "chunked_prefill_attention_tflops",
@@ -261,67 +406,42 @@ def main():
                                                            w.num_q_heads, w.head_dim, w.num_kv_heads, w.page_size,
                                                            w.seed),
             "chunk_size": C, "launch_mode": args.mode, "kv_export_in_step": args.export,
-            "segments_per_chunk": {"mean": round(float(np.mean([len(pipe.chunk_segments(c)) for c in range(nC)])), 2),
-                                   "max": int(max(len(pipe.chunk_segments(c)) for c in range(nC)))},
+            "cache": ("cold: steps rotate over %d independent sets of buffers, %d bytes touched between repeats" % (
+                n_sets, int(per_set * (n_sets - 1)))) if n_sets > 1 else "warm: one set of buffers",
+            "buffer_sets": n_sets,
+            "segments_per_chunk": {"mean": round(float(np.mean([len(s) for s in segs_of])), 2),
+                                   "max": int(max(len(s) for s in segs_of))},
             "step": "pack + metadata + upload + per chunk " +
                     ("(attention launch, kv append launch)" if args.two_launches else "one fused attention+append launch"),
         },
+        "warm_cache": warm,
         "roofline": {
             "bound": "mfma", "kernel": "attn_tile_kernel" + ("" if args.two_launches else " (with fused kv append)"),
             "achieved": round(achieved_tflops, 3), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved_tflops / PEAK_BF16_MFMA_TFLOPS, 5),
             "avg_launch_ms": round(attn_avg_ms, 5), "flops_per_launch": attn_flops_per_launch,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "two" if args.two_launches else "fused")),
-            "algorithmic_bytes_per_launch": float(np.mean([pipe.attn_bytes(c) + (0 if args.two_launches else
-                                                           pipe.append_bytes(c)) for c in range(n_meas)])),
+            "launches_timed": "groups of %d graph-replayed launches rotating over %d buffer set(s)" % (R, n_sets),
+            "traffic": traffic, "traffic_source": traffic_src,
+            "algorithmic_bytes_per_launch": float(np.mean(launch_bytes)),
+            "per_chunk_bound": ["mfma" if mfma_s[c] >= hbm_s[c] else "hbm" for c in range(n_meas)],
+            "per_chunk_bound_frac": [round(x, 4) for x in bound_frac],
         },
         "per_chunk": {
-            "attn_ms_median": [round(float(x), 5) for x in attn_med],
-            "attn_ms_p10": [round(spread[i][0], 5) for i in range(len(attn_med))],
-            "attn_ms_p90": [round(spread[i][1], 5) for i in range(len(attn_med))],
-            "attn_tflops": [round(flops[c] / (float(attn_med[c]) * 1e-3) / 1e12, 2) for c in range(len(attn_med))],
-            "append_ms_median": [round(float(x), 5) for x in app_med],
+            "attn_ms_median": [round(float(x), 5) for x in attn_ms],
+            "attn_ms_p10": [round(spread[i][0], 5) for i in range(len(attn_ms))],
+            "attn_ms_p90": [round(spread[i][1], 5) for i in range(len(attn_ms))],
+            "attn_tflops": [round(flops[c] / (float(attn_ms[c]) * 1e-3) / 1e12, 2) for c in range(len(attn_ms))],
+            "append_ms_median": [round(float(x), 5) for x in app_ms],
         },
         "append": {"kernel": "kv_append_kernel (stand-alone launch)", "avg_launch_ms": round(app_avg_ms, 5),
                    "achieved_GBs": round(app_bytes / (app_avg_ms * 1e-3) / 1e9, 1), "peak_GBs": PEAK_HBM_GBS,
                    "frac": round(app_bytes / (app_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }
-
-    # ---- cold cache: the same step rotated over independent copies of every buffer (inputs, output, page pool), so
-    # that more than twice the 256 MB last-level cache is touched before a buffer comes round again.  In a model
-    # the chunk's own rows are warm (the projection just wrote them) and the cached context is cold; `value` above
-    # has everything warm, this figure everything cold.
-    per_set = (q.numel() + k.numel() + v.numel() + out.numel()) * 2 + sum(w.prompt_lens) * 2 * w.num_kv_heads * w.head_dim * 2
-    n_sets = int(min(16, max(4, -(-(600 << 20) // per_set) + 1)))
-    if n_sets * (pool.numel() * 2 + per_set) <= (64 << 30) and not args.export:
-        sets = [pipe]
-        keep = []
-        for _ in range(n_sets - 1):
-            pp = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
-                                 w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
-                                 use_graph=(args.mode == "graph"), fused=not args.two_launches)
-            if args.variant is not None:
-                pp.handle.tetri_set_option("attn_variant", args.variant)
-            for kv in args.opt:
-                key, value = kv.split("=")
-                pp.handle.tetri_set_option(key, int(value))
-            bufs = (q.clone(), k.clone(), v.clone(), pool.clone(), torch.zeros_like(out))
-            pp.bind(*bufs)
-            keep.append(bufs)
-            sets.append(pp)
-        cold_steps = max(n_sets * 4, min(args.steps, 200) // n_sets * n_sets)
-        for i in range(2 * n_sets):
-            sets[i % n_sets].step()
-        torch.cuda.synchronize()
-        tc0 = time.perf_counter()
-        for i in range(cold_steps):
-            sets[i % n_sets].step()
-        torch.cuda.synchronize()
-        cold_ms = (time.perf_counter() - tc0) * 1e3 / cold_steps
-        result["cold_cache"] = {"value": round(total_flops / (cold_ms * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
-                                "ms_per_step": round(cold_ms, 5), "steps": cold_steps, "buffer_sets": n_sets,
-                                "bytes_touched_between_repeats": int(per_set * (n_sets - 1))}
-        del sets, keep
+    # what the last step left in set 0's output, for the check against the oracle below
+    pipe.step()
+    torch.cuda.synchronize()
+    out_host = out.float().cpu().numpy()
+    del sets[1:], keep
 
     # ---- the step after the hot path: request-level KV export of the whole batch and its import on a
     # receiver (Sec. 3.3.4), timed like the kernels above; moved bytes = payload read + payload written
@@ -332,8 +452,8 @@ def main():
         d_bt = torch.from_numpy(np.ascontiguousarray(pipe.req_bt)).to(dev)
         d_cu = torch.from_numpy(np.concatenate([[0], np.cumsum(w.prompt_lens)]).astype(np.int32)).to(dev)
         xbuf = torch.zeros(payload // 2, dtype=torch.bfloat16, device=dev)
-        exp_ms = group_time(lambda: pipe.handle.tetri_kv_export(pool, d_bt, d_cu, None, n_req, total_tokens, xbuf))
-        imp_ms = group_time(lambda: pipe.handle.tetri_kv_import(xbuf, d_bt, d_cu, None, n_req, total_tokens, pool))
+        exp_ms = group_time(lambda i: pipe.handle.tetri_kv_export(pool, d_bt, d_cu, None, n_req, total_tokens, xbuf))
+        imp_ms = group_time(lambda i: pipe.handle.tetri_kv_import(xbuf, d_bt, d_cu, None, n_req, total_tokens, pool))
         result["kv_transfer"] = {
             "kernel": "kv_transfer_kernel (request-level, %d request(s), %d tokens)" % (n_req, total_tokens),
             "payload_bytes": payload, "bound": "hbm", "peak_GBs": PEAK_HBM_GBS,
@@ -360,7 +480,7 @@ def main():
         dout = torch.zeros_like(dq)
         dbt = torch.from_numpy(np.random.default_rng(w.seed).permutation(dB * d_need).astype(np.int32).reshape(dB, d_need)).to(dev)
         dcl = torch.full((dB,), dctx, dtype=torch.int32, device=dev)
-        dec_ms = group_time(lambda: dh.tetri_decode_attn(dq, dk, dv, dpool, dbt, dcl, dB, dctx, w.scale, dout))
+        dec_ms = group_time(lambda i: dh.tetri_decode_attn(dq, dk, dv, dpool, dbt, dcl, dB, dctx, w.scale, dout))
         result["decode"] = {
             "kernel": "decode_attn_kernel (%d requests x %d cached tokens, %dx%d query heads, %d kv heads)" % (
                 dB, dctx, w.num_q_heads, w.head_dim, w.num_kv_heads),
@@ -371,8 +491,8 @@ def main():
         }
         # the same iteration over an FP8 E4M3 cache (this build's extension): half the bytes
         dcodes = torch.randint(0, 0x78, tuple(dpool.shape), dtype=torch.uint8, device=dev, generator=gen)
-        dec8_ms = group_time(lambda: dh.tetri_decode_attn_fp8(dq, dk, dv, dcodes, dbt, dcl, dB, dctx, w.scale,
-                                                              1.0 / 64, 1.0 / 64, 0, dout))
+        dec8_ms = group_time(lambda i: dh.tetri_decode_attn_fp8(dq, dk, dv, dcodes, dbt, dcl, dB, dctx, w.scale,
+                                                                1.0 / 64, 1.0 / 64, 0, dout))
         result["decode"]["fp8"] = {
             "kernel": "decode_attn_kernel<D, FP8> (same batch, cache of E4M3 codes)", "kv_bytes": kv_bytes // 2,
             "ms": round(dec8_ms, 5), "achieved_GBs": round(kv_bytes / 2 / (dec8_ms * 1e-3) / 1e9, 1),
@@ -388,21 +508,20 @@ def main():
         from oracle import packer as opacker
         lib = tetri_oracle.load()
         threads = os.cpu_count() or 1
+        omp = None
         try:
             import ctypes
             omp = ctypes.CDLL("libgomp.so.1")
             threads = int(omp.omp_get_max_threads())
         except OSError:
             pass
-        # bounded sample: whole chunks of the same workload until about 10 s of CPU work
         plan = opacker.pack_chunks(w.prompt_lens, w.order, C)
-        opool = np.zeros((w.num_pages if w.num_pages <= 4096 else 1, 2, w.num_kv_heads, w.page_size, w.head_dim),
-                         dtype=np.float32)
-        sample_flops, cpu_s, n_done, worst = 0.0, 0.0, 0, 0.0
-        out_host = out.float().cpu().numpy()
+        max_blocks = max(len(t) for t in tables)
         if w.num_pages <= 4096:
+            # small pool: whole chunk passes of the same workload (attention + append, all heads) until about 10 s
+            opool = np.zeros((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), dtype=np.float32)
+            sample_flops, cpu_s, n_done, worst = 0.0, 0.0, 0, 0.0
             qh, kh, vh = q.float().cpu().numpy(), k.float().cpu().numpy(), v.float().cpu().numpy()
-            max_blocks = max(len(t) for t in tables)
             n_pass = 0
             while cpu_s < 10.0 and n_pass < 50:
                 opool[:] = 0
@@ -430,23 +549,76 @@ def main():
             }
             result["parity_check"] = {"max_abs_vs_oracle": round(worst, 6), "chunks": min(n_done, nC)}
             # one thread: the first chunk of the same workload, once (if the OpenMP runtime lets the count be set)
-            try:
-                omp.omp_set_num_threads(1)
-                cu0, ctx0 = opacker.chunk_arrays(plan[0])
-                bt0 = np.zeros((len(plan[0]), max_blocks), dtype=np.int32)
-                for i, (req, _s, _n) in enumerate(plan[0]):
-                    bt0[i, :len(tables[req])] = tables[req]
-                opool[:] = 0
-                ts = time.perf_counter()
-                tetri_oracle.chunk_prefill_attn(qh[0], kh[0], vh[0], opool, bt0, cu0, ctx0, w.scale, lib=lib)
-                one_s = time.perf_counter() - ts
-                omp.omp_set_num_threads(threads)
-                result["cpu_baseline"]["single_thread"] = {"value": round(flops[0] / one_s / 1e12, 6), "unit": "TFLOP/s",
-                                                           "sample": "attention of chunk 0, once", "seconds": round(one_s, 3)}
-            except (NameError, AttributeError):
-                pass
+            if omp is not None:
+                try:
+                    omp.omp_set_num_threads(1)
+                    cu0, ctx0 = opacker.chunk_arrays(plan[0])
+                    bt0 = np.zeros((len(plan[0]), max_blocks), dtype=np.int32)
+                    for i, (req, _s, _n) in enumerate(plan[0]):
+                        bt0[i, :len(tables[req])] = tables[req]
+                    opool[:] = 0
+                    ts = time.perf_counter()
+                    tetri_oracle.chunk_prefill_attn(qh[0], kh[0], vh[0], opool, bt0, cu0, ctx0, w.scale, lib=lib)
+                    one_s = time.perf_counter() - ts
+                    omp.omp_set_num_threads(threads)
+                    result["cpu_baseline"]["single_thread"] = {"value": round(flops[0] / one_s / 1e12, 6), "unit": "TFLOP/s",
+                                                               "sample": "attention of chunk 0, once", "seconds": round(one_s, 3)}
+                except AttributeError:
+                    pass
         else:
-            result["cpu_baseline"] = None
+            # large pool (the 16K-token prompt, the GQA batch): the oracle computes sampled (row, head) outputs of a few
+            # chunks one by one, the cached context rebuilt in a compact pool with the oracle's own append (the
+            # result does not depend on where the pages lie).  Chunks: for a batch, those that hold the two shortest
+            # prompts and the longest prompt's last chunk; for one prompt the first, middle and last chunk.  All real
+            # rows, every eighth query head.  Stops taking chunks after 30 s.
+            by_len = np.argsort(w.prompt_lens, kind="stable")
+            if len(w.prompt_lens) > 2:
+                want = {int(by_len[0]), int(by_len[1])}
+                chunks = [c for c, s in enumerate(plan) if any(r in want for r, _a, _n in s)][:4]
+                chunks.append(max(c for c, s in enumerate(plan) if any(r == int(by_len[-1]) for r, _a, _n in s)))
+                chunks = sorted(set(chunks))
+            else:
+                chunks = sorted({0, nC // 2, nC - 1})
+            heads = np.arange(0, w.num_q_heads, 8, dtype=np.int32)
+            cpu_s, sample_flops, worst, n_samples, done = 0.0, 0.0, 0.0, 0, []
+            P, Hkv, D = w.page_size, w.num_kv_heads, w.head_dim
+            for c in chunks:
+                if cpu_s > 30.0:
+                    break
+                segs = plan[c]
+                need = [-(-(start + n) // P) for _req, start, n in segs]
+                cpool = np.zeros((max(1, sum(need)), 2, Hkv, P, D), dtype=np.float32)
+                bt = np.zeros((len(segs), max(need)), dtype=np.int32)
+                at = 0
+                for i, (req, start, n) in enumerate(segs):
+                    bt[i, :need[i]] = np.arange(at, at + need[i])
+                    at += need[i]
+                    if start > 0:
+                        _rq, rk, rv = host_reqs[req] if req in host_reqs else synth.request_qkv(w, req)
+                        tetri_oracle.kv_append(rk[:start].float().numpy(), rv[:start].float().numpy(), cpool, bt[i:i + 1],
+                                               np.array([0, start], dtype=np.int32), np.array([0], dtype=np.int32), lib=lib)
+                cu, ctx = opacker.chunk_arrays(segs)
+                n_real = int(cu[-1])
+                rows = np.repeat(np.arange(n_real, dtype=np.int32), len(heads))
+                hh = np.tile(heads, n_real)
+                qc, kc, vc = q[c].float().cpu().numpy(), k[c].float().cpu().numpy(), v[c].float().cpu().numpy()
+                ts = time.perf_counter()
+                ref = tetri_oracle.chunk_prefill_attn_samples(qc, kc, vc, cpool, bt, cu, ctx, w.scale, rows, hh, lib=lib)
+                cpu_s += time.perf_counter() - ts
+                sample_flops += flops[c] * len(heads) / w.num_q_heads
+                n_samples += len(rows)
+                done.append(c)
+                worst = max(worst, float(np.abs(ref - out_host[c][rows, hh]).max()))
+            cpu_tflops = sample_flops / cpu_s / 1e12
+            result["cpu_baseline"] = {
+                "value": round(cpu_tflops, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle", "seconds": round(cpu_s, 3),
+                "sample": "attention of chunks %s of the same workload: all real rows, query heads %s (%d (row, head) outputs, "
+                          "%.1f GFLOP of the workload's %.1f)" % (done, [int(x) for x in heads], n_samples, sample_flops / 1e9,
+                                                                total_flops / 1e9),
+                "whole_workload_seconds_extrapolated": round(total_flops / (cpu_tflops * 1e12), 1),
+                "extrapolation": "the workload's flops / the sample's rate: an estimate, not a measurement",
+            }
+            result["parity_check"] = {"max_abs_vs_oracle": round(worst, 6), "chunks": done, "samples": n_samples}
     if args.calib_copy:
         a = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.ones(256 << 20, dtype=torch.uint8, device=dev)

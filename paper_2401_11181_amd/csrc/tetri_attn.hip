@@ -339,9 +339,6 @@ __device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf
 {
     constexpr int DBLK = D / 32;
     constexpr size_t STATS = (size_t)DBLK * 4 * 64 * 16;
-#ifdef TETRI_EXP_NOFINISH
-    return;
-#endif
     const int half = lane >> 5, l32 = lane & 31;
     float macc = 0.f, lacc = 0.f;
     f32x16 acc[DBLK];
@@ -915,9 +912,6 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     f32x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
-#ifdef TETRI_EXP_NOSTORE
-                    if (!next)
-#endif
                     store_coherent(po + (db * 4 + q4) * 64 + lane, x);
                 }
             float *ps = reinterpret_cast<float *>(mine + (size_t)DBLK * 4 * 64 * 16);

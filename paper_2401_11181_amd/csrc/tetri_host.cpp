@@ -431,7 +431,9 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
         // (the last tile of the bound and its helper exist only in chunks with ragged segments and are not counted)
         if (p.tiles >= 2 && (int64_t)(p.tiles - 1 + helpers - 1) * groups <= cus && (size_t)p.tiles * groups * 4 <= h->scratch_units)
             p.helpers = helpers;
-        else if ((int64_t)p.tiles * groups < 2 * (int64_t)cus)
+        // (segments of under 256 rows on average are a batch of short prompts: a handful of stages per tile, which
+        // the division would only cut into smaller pieces)
+        else if ((int64_t)p.tiles * groups < 2 * (int64_t)cus && (int64_t)p.C >= 256 * (int64_t)p.S)
             G = std::min(255, (cus - (kv_pages_w ? 8 : 0)) / groups);
     }
     const int stage = 64 * key_parts;

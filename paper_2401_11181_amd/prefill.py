@@ -87,14 +87,6 @@ class ChunkedPrefill:
         cu, ctx, bt, S = self.meta[c]
         self.handle.tetri_validate_chunk(bt, cu, ctx, S)
 
-    def pairs(self, c):
-        """Unmasked (query, key) pairs per query head of chunk c: sum n*L + n(n+1)/2."""
-        return sum(n * start + n * (n + 1) // 2 for _req, start, n in self.chunk_segments(c))
-
-    def flops(self, c):
-        """Algorithmic attention flops of chunk c: 4 * D * Hq * pairs (QK^T and PV, masked pairs count zero)."""
-        return 4 * self.D * self.Hq * self.pairs(c)
-
 
 class PrefillPipeline:
     """The whole hot path of one scheduled batch as a repeatable step, for measurement.
@@ -261,24 +253,6 @@ class PrefillPipeline:
         else:
             self._launch_all()
 
-    # --- bookkeeping ----------------------------------------------------------------------------
+    # --- the plan -------------------------------------------------------------------------------
     def chunk_segments(self, c):
         return [tuple(int(v) for v in s) for s in self.plan_segs[self.plan_offsets[c]:self.plan_offsets[c + 1]]]
-
-    def pairs(self, c):
-        return sum(n * start + n * (n + 1) // 2 for _req, start, n in self.chunk_segments(c))
-
-    def flops(self, c):
-        return 4 * self.D * self.Hq * self.pairs(c)
-
-    def attn_bytes(self, c):
-        """Algorithmic HBM bytes of one attention launch: Q in + out, K and V once, block table."""
-        segs = self.chunk_segments(c)
-        n = sum(x[2] for x in segs)
-        kv = sum((start + ln) * self.Hkv * self.D * 2 * 2 for _r, start, ln in segs)
-        bt = sum(-(-start // 16) * 4 for _r, start, _ln in segs)
-        return 2 * n * self.Hq * self.D * 2 + kv + bt
-
-    def append_bytes(self, c):
-        n = sum(x[2] for x in self.chunk_segments(c))
-        return 2 * 2 * n * self.Hkv * self.D * 2

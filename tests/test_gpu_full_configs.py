@@ -8,6 +8,8 @@ segment of a checked chunk, the rows on both sides of every 32-row block edge ne
 others, random rows elsewhere; for gqa additionally every row of four query heads in the chunks of the two
 shortest prompts and of the longest one.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -138,3 +140,16 @@ def test_gqa_config_sampled(oracle):
     print("gqa: two-segment chunks", two_segs, "dense chunks", dense, flush=True)
     print(run_sampled(oracle, w, check_chunks=[0, 8, 9, 30, 50, -2, -1] + two_segs, n_samples=48, seed=5,
                       dense_chunks=dense, dense_heads=(1, 10, 19, 28)))
+
+
+@pytest.mark.parametrize("chunk_size", [1024, 4096])
+def test_large_chunk_sizes_sampled(oracle, chunk_size):
+    """One 8192-token prompt on the 13B head shape (40 x 128) with ChunkSize 1024 and 4096: launches with more row
+    tiles than two thirds of the compute units.  With 1024 the library gives every head its share of workgroups
+    and divides the head's stages evenly among them (tiles of many pieces); with 4096 there are two whole tiles per
+    compute unit and four-wavefront workgroups."""
+    base = synth.workload("opt13b")
+    w = dataclasses.replace(base, name="opt13b-len8192-chunk%d" % chunk_size, prompt_lens=[8192], order=[0],
+                            chunk_size=chunk_size, num_pages=8192 // base.page_size + 64, seed=3000 + chunk_size)
+    n_chunks = 8192 // chunk_size
+    print(run_sampled(oracle, w, check_chunks=sorted({0, 1, n_chunks // 2, n_chunks - 1}), n_samples=96, seed=6))

@@ -45,6 +45,8 @@
 //         the next job are requested before the current job's epilogue.
 //   * The fused form of the launch has further workgroups that copy the chunk's new K/V rows
 //     into the page pool (append_rows).
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace {
@@ -63,11 +65,19 @@ constexpr int kBNW = 64;      // keys per wavefront per stage
 template <int D>
 struct LaneOffsets {
     uint32_t k_ctx, v_ctx;      // rows 512 (256) bytes apart inside a (page, head) block of the pool
-    uint32_t new_extra;         // what a lane's row is further away in k_new / v_new, whose rows are Hkv*D*2 bytes apart
 };
 
+// The lane index, read anew from the thread id.  Values derived from it where they are needed do not occupy
+// registers across the main loop, which has none to spare.
+__device__ __forceinline__ int fresh_lane()
+{
+    int x = threadIdx.x;
+    asm volatile("" : "+v"(x));
+    return x & 63;
+}
+
 template <int D>
-__device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane, int new_row_bytes)
+__device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane)
 {
     constexpr int CH = D / 8;
     const int r0 = lane / CH;                                    // row of instruction 0
@@ -75,7 +85,6 @@ __device__ __forceinline__ void init_lane_offsets(LaneOffsets<D> &lo, int lane, 
     const int vc = (lane % CH) ^ v_swizzle<D>(r0);
     lo.k_ctx = r0 * D * 2 + kc * 16;
     lo.v_ctx = r0 * D * 2 + vc * 16;
-    lo.new_extra = r0 * (new_row_bytes - D * 2);
 }
 // XOR that turns instruction 0's chunk into instruction i's (in bytes).
 template <int D> __host__ __device__ __forceinline__ constexpr uint32_t k_inst_xor(int i)
@@ -169,8 +178,10 @@ __device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const Wa
     sl.j0 = (ctx ? it : jn) * STAGE + 16 * wave;
     sl.limit = ctx ? src.L : src.n_new;
     sl.kdst = k_lds + wave * (16 * D * 2);
-    sl.ko = lo.k_ctx + (ctx ? 0u : lo.new_extra);
-    sl.vo = lo.v_ctx + (ctx ? 0u : lo.new_extra);
+    // (a lane's row is further away in k_new / v_new, whose rows are Hkv*D*2 bytes apart, than in a page)
+    const uint32_t new_extra = ctx ? 0u : (uint32_t)(fresh_lane() / (D / 8)) * (uint32_t)(new_row_bytes - D * 2);
+    sl.ko = lo.k_ctx + new_extra;
+    sl.vo = lo.v_ctx + new_extra;
     // pool rows of an instruction follow the previous one's directly (the immediate offset covers
     // it); rows of k_new / v_new are `step` bytes further apart than that
     if (ctx) {
@@ -188,7 +199,7 @@ __device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const Wa
 
 // All loads of a stage at once.
 template <int D, int KS>
-__device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool full, int lane)
+__device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool full)
 {
     constexpr int CH = D / 8, RPI = 64 / CH, NI = 16 / RPI;
     constexpr uint32_t V_LDS = 2 * (kBNW * KS) * D * 2;
@@ -206,6 +217,7 @@ __device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool ful
     } else {
         // ragged end of the key range: rows past the limit come from a row of zeros
         const char *zero = reinterpret_cast<const char *>(g_zero_row);
+        const int lane = fresh_lane();
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const bool ok = sl.j0 + RPI * i + lane / CH < sl.limit;
@@ -485,14 +497,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     const int it_begin = J.it_begin, n_stages = J.it_end;      // end of this piece's stage range
     const int par = __builtin_amdgcn_readfirstlane(cy.par);
 
-    const int tw0 = J.t0 + 32 * rbk;       // first local row of this wavefront
-    const int t = tw0 + l32;               // local row of this lane's query
-    const bool row_ok = t < n_s;
+    const int tw0 = J.t0 + 32 * rbk;       // first local row of this wavefront; lane l's query is local row tw0 + l % 32
     const bool wave_has_rows = tw0 < n_s;
 
     const int new_row_bytes = p.Hkv * D * 2;
     LaneOffsets<D> lo;
-    init_lane_offsets<D>(lo, lane, new_row_bytes);
+    init_lane_offsets<D>(lo, lane);
     const uint32_t smem_lds = lds_address(smem);
     constexpr uint32_t STAGE_BYTES = STAGE_U4 * 16;   // bytes of one matrix of one stage
 
@@ -503,7 +513,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // of a SIMD use different ones), so that at any time most wavefronts are computing.
     StageLoads sl;
     bool pend = false;                               // the next stage's loads are described in sl, not issued
-    const int load_point = (wave + (kq != 0 ? 2 : 0)) & 3;
+    const int load_point = __builtin_amdgcn_readfirstlane((wave + (kq != 0 ? 2 : 0)) & 3);
     int page = __builtin_amdgcn_readfirstlane(cy.page);
     // the pages of this wavefront's rows of the next job's first two stages: asked for now, needed after the loop
     int page_n0 = 0, page_n1 = 0;
@@ -525,8 +535,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     float lsum = 0.f;        // this lane's share of the running row sum
     // scores are multiplied by c = scale * log2(e), of either sign; a masked score is the infinity
     // that c turns into -inf
-    const float c = p.neg ? -p.c : p.c;
-    const float masked = p.neg ? INFINITY : -INFINITY;
+    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.neg ? -p.c : p.c)));
     const int blk = lane >> 4, i16 = lane & 15;
 
     // Fragment loads from LDS.  K: lane holds key (row) l32 of a 32-key block, d = 16*st + 8*half .. +7
@@ -592,13 +601,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // the next stage is entered.
     auto issue_pending = [&](int point) {
         if (pend && load_point == point) {
-            issue_stage_loads<D, KS>(sl, true, lane);
+            issue_stage_loads<D, KS>(sl, true);
             pend = false;
         }
     };
     auto sync_stage = [&](int it) -> int {
         if (pend) {                                    // rare: the stage had too few blocks to reach the point
-            issue_stage_loads<D, KS>(sl, true, lane);
+            issue_stage_loads<D, KS>(sl, true);
             pend = false;
         }
         wait_vm<0>();
@@ -610,7 +619,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         if (it + 1 < n_stages) {
             const bool full = describe_stage_loads<D, KS>(src, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
             if (full && pv_before && nb != 0 && load_point != 0) pend = true;
-            else issue_stage_loads<D, KS>(sl, full, lane);
+            else issue_stage_loads<D, KS>(sl, full);
         }
         page = load_stage_page<KS>(bt_row, ws.max_blocks, it + 2, wave);
     };
@@ -639,11 +648,11 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     bool stashed = true;    // (a register kept across all jobs would be spilled to memory)
     auto announce = [&]() {
         if (!stashed) {
-            if (lane == 0) old_stash[slot] = old;
+            if (fresh_lane() == 0) old_stash[slot] = old;
             stashed = true;
         }
         if (ho.unit >= 0 && !ho.announced) {
-            if (lane == 0) old = atomicAdd(p.counters + ho.unit, 1);
+            if (fresh_lane() == 0) old = atomicAdd(p.counters + ho.unit, 1);
             ho.announced = true;
             stashed = false;
         }
@@ -694,7 +703,11 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // are in kf; discarded after the last block) on the matrix cores, interleaved with
         // exponentiating and rounding this block's weights on the VALU against the reference exponent
         // m the row already has; then the PV product with the V fragments in vf.
-        auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, const s16x8 (&vf)[2 * DBLK]) {
+        // v_off: where in LDS the block's V fragments are, if they are still to be read (spread between the score
+        // products, behind the K fragments those wait for); a negative value: vf holds them already.
+        // at_point(1), at_point(2): two of the places where a wavefront may issue the next stage's loads.
+        auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, s16x8 (&vf)[2 * DBLK], auto v_off, auto &&at_point) {
+            constexpr int V_OFF = decltype(v_off)::value;
             bf16x8 pf[2];
             float l_blk;
             if constexpr (KS == 1) {
@@ -705,24 +718,33 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 // slots in between (measured: +7 to +13 % on launches with two workgroups per compute unit; for
                 // eight-wavefront workgroups, whose SIMD partners meet at every barrier, no gain).
                 __builtin_amdgcn_sched_barrier(0);
+                if constexpr (V_OFF >= 0) load_v(vf, V_OFF);
                 l_blk = weights(s_cur, pf);
                 __builtin_amdgcn_sched_barrier(0);
-                issue_pending(1);
+                at_point(1);
                 __builtin_amdgcn_s_setprio(3);
                 s_next = qk(kf);
                 __builtin_amdgcn_sched_barrier(0);
             } else {
                 __builtin_amdgcn_sched_barrier(0);
                 s_next = qk(kf);
+                if constexpr (V_OFF >= 0) load_v(vf, V_OFF);
                 l_blk = weights(s_cur, pf);
-                // wanted order: one MFMA of the score chain, then its share of the VALU operations, 8 times
+                // wanted order: one MFMA of the score chain, then its share of the LDS reads and of the VALU
+                // operations (exponentials are a class of their own), 8 times
 #pragma unroll
                 for (int g = 0; g < KSTEPS; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 48 / KSTEPS, 0);
+                    if constexpr (V_OFF >= 0) __builtin_amdgcn_sched_group_barrier(0x100, 4 * DBLK / KSTEPS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 16 / KSTEPS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x400, 16 / KSTEPS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 16 / KSTEPS, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                issue_pending(1);
+                // (the weights are needed here: computed in front of the branch below, inside the region the
+                // order above applies to, not moved behind it)
+                asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(l_blk));
+                at_point(1);
             }
             // m is only a reference point, not the exact row maximum: any value keeps the result exact
             // as long as the weights stay in range.  Only when a lane's weights of this block sum to
@@ -755,12 +777,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
-                if (KS != 1 && j == 0) issue_pending(2);
+                if (KS != 1 && j == 0) at_point(2);
             }
             if constexpr (KS == 1) {
                 __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
-                issue_pending(2);
+                at_point(2);
             }
         };
         // One block: scores s_cur are ready; computes s_next for the block after it.  Returns false
@@ -769,7 +791,6 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             const bool is_ctx = it < src.n_ctx_tiles;
             const int key0 = (is_ctx ? it : it - src.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
             const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
-            const int bound = is_ctx ? L - 1 : t;      // last visible key index of this phase
             // V fragments of this block: in registers before the stage may be left
             s16x8 vf[2 * DBLK];
             load_v(vf, buf_of(it) + kb * BLOCK_BYTES);
@@ -794,17 +815,68 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             // ---- mask: accumulator element v is key key0 + (v/4)*8 + 4*half + v%4; keys past `bound`
             // (the end of the cached context, or the query's own position) get weight exp2(-inf) = 0
             if (need_mask) {
+                const int ln = fresh_lane();
+                const int bound = is_ctx ? L - 1 : tw0 + (ln & 31);       // last visible key index of this phase
+                const float masked = c < 0.f ? INFINITY : -INFINITY;     // the infinity that c turns into -inf
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + (v / 4) * 8 + 4 * half + (v % 4);
+                    const int key = key0 + (v / 4) * 8 + 4 * (ln >> 5) + (v % 4);
                     if (key > bound) s_cur[v] = masked;
                 }
             }
-            softmax_pv(s_cur, s_next, vf);
+            softmax_pv(s_cur, s_next, vf, std::integral_constant<int, -1>(), issue_pending);
             return have_next;
         };
+        // ---- steady state.  Most of a long key range is whole stages of cached keys: both of the wavefront's
+        // blocks exist, nothing is masked, all 16 rows the wavefront loads exist, and after the job's first
+        // stages no announcement is pending.  Two such stages are one trip of a loop in which all of that is
+        // known: the stage buffers alternate at compile time (LDS offsets are instruction immediates), a stage's
+        // loads are its page base plus constants, and no block asks what kind of block it is.  The general
+        // blocks below take over with the same state wherever one of the conditions does not hold.
+        // step<B>: on entry stage `it` is in buffer B, s_a holds the scores of its first block and the loads of stage
+        // it + 1 are issued; on exit the same holds for stage it + 1 in buffer 1 - B.
         f32x16 s_a = qk(kf), s_b;
+        auto steady_step = [&](auto buffer) {
+            constexpr int cur = decltype(buffer)::value * (int)STAGE_BYTES, nxt = (int)STAGE_BYTES - cur;
+            s16x8 vf[2 * DBLK];
+            load_k(kf, cur + BLOCK_BYTES);
+            softmax_pv(s_a, s_b, vf, std::integral_constant<int, cur>(), [](int) {});
+            load_v(vf, cur + BLOCK_BYTES);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS: the stage may be left
+            ++it;
+            wait_vm<0>();
+            __syncthreads();
+            load_k(kf, nxt);
+            const int pg = page;                                 // of stage it + 1, which goes where stage it - 1 was
+            page = load_stage_page<KS>(bt_row, ws.max_blocks, it + 2, wave);
+            auto loads_at = [&](int point) {
+                if (load_point == point) {
+                    StageLoads st;
+                    st.kb = ws.pool_k + (size_t)pg * ws.page_bytes;
+                    st.vb = st.kb + ws.v_delta;
+                    st.step = 0;
+                    st.kdst = smem_lds + cur + wave * (16 * D * 2);
+                    st.ko = lo.k_ctx;
+                    st.vo = lo.v_ctx;
+                    issue_stage_loads<D, KS>(st, true);
+                }
+            };
+            loads_at(0);
+            softmax_pv(s_b, s_a, vf, std::integral_constant<int, -1>(), loads_at);
+            loads_at(3);
+        };
+        const int steady_end = min(n_stages, L / STAGE);       // stages before it are whole stages of cached keys
         for (;;) {
+            if (kb == 0 && nblk == NKB && buf_of(it) == 0 && it + 3 < steady_end && stashed && (ho.unit < 0 || ho.announced)) {
+                if (pend) {
+                    issue_stage_loads<D, KS>(sl, true);
+                    pend = false;
+                }
+                do {
+                    steady_step(std::integral_constant<int, 0>());
+                    steady_step(std::integral_constant<int, 1>());
+                } while (it + 3 < steady_end);
+            }
             if (!block(s_a, s_b)) break;
             if (!block(s_b, s_a)) break;
         }
@@ -814,7 +886,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     if (next) {
         const bool full = describe_stage_loads<D, KS>(nsrc, ws, lo, page_n0, n_it_begin, wave, new_row_bytes,
                                                       smem_lds + (buf_of(n_stages - 1) ^ STAGE_BYTES), sl);
-        issue_stage_loads<D, KS>(sl, full, lane);
+        issue_stage_loads<D, KS>(sl, full);
     }
     if (ho.unit >= 0 && (!ho.announced || !stashed)) {        // a partial result not announced, or announced at the job's last stage
         wait_vm<0>();
@@ -829,8 +901,11 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // ---- the next job: its Q rows are requested now, so that they arrive during this job's epilogue
     asm volatile("" ::: "memory");                   // a fresh read, not the values from before the loop
     const AttnParams pe = read_params(params);
+    const int lane_e = fresh_lane(), half_e = lane_e >> 5, l32_e = lane_e & 31;
+    const int t_e = tw0 + l32_e;                     // local row of this lane's query
+    const bool row_ok_e = t_e < n_s;
     if (next) {
-        request_q<D>(pe, N, head, rbk, lane, cy.qf);
+        request_q<D>(pe, N, head, rbk, lane_e, cy.qf);
         cy.par = ((n_stages & 1) ^ par) ^ (n_it_begin & 1);      // its first stage goes where stage n_stages of this job would
         cy.page = page_n1;
     }
@@ -865,14 +940,14 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     f32x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
-                    part[(db * 4 + q4) * 64 + lane] = x;
+                    part[(db * 4 + q4) * 64 + lane_e] = x;
                 }
-            if (half == 0) { Mstat[slot][0][l32] = m; Mstat[slot][1][l32] = ltot; }
+            if (half_e == 0) { Mstat[slot][0][l32_e] = m; Mstat[slot][1][l32_e] = ltot; }
         }
         lds_barrier();
         TETRI_MARK((first_job ? 0 : 12) + 5);
         if (kq == 1) return;
-        const float m1 = Mstat[slot][0][l32], l1 = Mstat[slot][1][l32];
+        const float m1 = Mstat[slot][0][l32_e], l1 = Mstat[slot][1][l32_e];
         const float mstar = fmaxf(m, m1);
         const float w0 = __builtin_amdgcn_exp2f(m - mstar), w1 = __builtin_amdgcn_exp2f(m1 - mstar);
         ltot = ltot * w0 + l1 * w1;
@@ -882,7 +957,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 x = part[(db * 4 + q4) * 64 + lane];
+                const f32x4 x = part[(db * 4 + q4) * 64 + lane_e];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[db][q4 * 4 + e] = o[db][q4 * 4 + e] * w0 + x[e] * w1;
             }
@@ -899,7 +974,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         bool all_there = false;
         if (!next) {
             wait_vm<0>();
-            all_there = __builtin_amdgcn_readfirstlane(peek[slot][lane]) == J.npieces - 1;
+            all_there = __builtin_amdgcn_readfirstlane(peek[slot][lane_e]) == J.npieces - 1;
         }
         if (!all_there) {
             // leave (O, m, row sum) in the scratch memory ...
@@ -912,10 +987,10 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     f32x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
-                    store_coherent(po + (db * 4 + q4) * 64 + lane, x);
+                    store_coherent(po + (db * 4 + q4) * 64 + lane_e, x);
                 }
             float *ps = reinterpret_cast<float *>(mine + (size_t)DBLK * 4 * 64 * 16);
-            if (half == 0) { store_coherent(ps + l32, m); store_coherent(ps + 32 + l32, ltot); }
+            if (half_e == 0) { store_coherent(ps + l32_e, m); store_coherent(ps + 32 + l32_e, ltot); }
             if (next) {
                 // ... and go on with the next job: neither the end of the stores nor the answer of the
                 // arrival counter is waited for here (about 4 us); the piece is announced after the next
@@ -930,7 +1005,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             }
             coherent_stores_done();                  // this wavefront's partial is in memory ...
             int arrived = 0;
-            if (lane == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
+            if (lane_e == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
             arrived = __builtin_amdgcn_readfirstlane(arrived);
             if (arrived != J.npieces - 1) {          // not the last one: whoever is finishes the tile
                 TETRI_MARK((first_job ? 0 : 12) + 6);
@@ -938,7 +1013,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             }
         }
         if (J.npieces == 2) {
-            finish_pair<D>(pe, grp, J.wf, J.tile_index, J.piece, slot, o, m, ltot, lane, row_ok, J.seg_cu + t, head);
+            finish_pair<D>(pe, grp, J.wf, J.tile_index, J.piece, slot, o, m, ltot, lane_e, row_ok_e, J.seg_cu + t_e, head);
         } else {
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
@@ -947,18 +1022,18 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     f32x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = o[db][q4 * 4 + e];
-                    part[(db * 4 + q4) * 64 + lane] = x;
+                    part[(db * 4 + q4) * 64 + lane_e] = x;
                 }
-            finish_tile<D>(pe, grp, J.wf, J.tile_index, J.npieces, J.piece, slot, part, m, ltot, lane, row_ok, J.seg_cu + t, head);
+            finish_tile<D>(pe, grp, J.wf, J.tile_index, J.npieces, J.piece, slot, part, m, ltot, lane_e, row_ok_e, J.seg_cu + t_e, head);
         }
         TETRI_MARK((first_job ? 0 : 12) + 6);
         return;
     }
 
     // ---- normalise and store: lane holds out[t][head][db*32 + (v/4)*8 + 4*half + v%4]
-    if (!row_ok) return;
+    if (!row_ok_e) return;
     const float inv = __builtin_amdgcn_rcpf(ltot);
-    uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t) * pe.Hq + head) * D;
+    uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t_e) * pe.Hq + head) * D;
 #pragma unroll
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -966,7 +1041,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             bf16x4 w;
 #pragma unroll
             for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
-            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
+            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half_e) = __builtin_bit_cast(uint2, w);
         }
     TETRI_MARK((first_job ? 0 : 12) + 6);
 }
@@ -1285,7 +1360,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     {
         const int new_row_bytes = p.Hkv * D * 2;
         LaneOffsets<D> lo;
-        init_lane_offsets<D>(lo, lane, new_row_bytes);
+        init_lane_offsets<D>(lo, lane);
         // entry e of the job's block-table row (clamped entries are never used)
         auto row_entry = [&](int e) -> int {
             e = min(e, p.max_blocks - 1);
@@ -1303,7 +1378,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             for (int part = 0; part < KS; ++part) {
                 const bool full = describe_stage_loads<D, KS>(J.src, ws, lo, part == 0 ? page : page_hi, J.it_begin, wave + part * kSlots,
                                                               new_row_bytes, lds_address(smem), sl);
-                issue_stage_loads<D, KS>(sl, full, lane);
+                issue_stage_loads<D, KS>(sl, full);
             }
         }
         cy.page = row_entry((J.it_begin + 1) * PPS + wave);

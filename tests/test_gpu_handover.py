@@ -137,6 +137,7 @@ def test_overlapping_launches_on_one_handle_are_refused(oracle):
         check(out_b, ref_rows, "whole tiles on the second stream")
         # the first stream has drained: the second one may now divide tiles on this handle
         out_b.zero_()
+        torch.cuda.synchronize()                            # (the fill runs on the default stream)
         sess.attn(c, q, k, v, pool, w.scale, out_b, stream=st_b)
         torch.cuda.synchronize()
         check(out_b, ref_rows, "second stream, after the first has drained")

@@ -566,16 +566,18 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         for (int st = 0; st < KSTEPS; ++st)
             kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(smem_b + kbase[st] + off));
     };
+    auto load_v_half = [&](s16x8 (&vf)[2 * DBLK], int off, int j) {        // the fragments of PV step j
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const char *a = smem_b + vbase[db] + off + j * (16 * D * 2);
+            const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
+            const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * D * 2));
+            vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
     auto load_v = [&](s16x8 (&vf)[2 * DBLK], int off) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db) {
-                const char *a = smem_b + vbase[db] + off + j * (16 * D * 2);
-                const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
-                const s16x4 vb4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * D * 2));
-                vf[j * DBLK + db] = __builtin_shufflevector(va, vb4, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
+        load_v_half(vf, off, 0);
+        load_v_half(vf, off, 1);
     };
 
     // Number of 32-key blocks of stage `it` this wavefront works on (a prefix of its 64-key part):
@@ -681,23 +683,33 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         bf16x8 kf[KSTEPS];
         load_k(kf, buf_of(it));
         next_stage_loads(it, nblk, false);
-        bf16x2 ones;
-        ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
         // weights of a block from its scores and the row's reference exponent m: bf16-rounded, laid out
-        // as the B operand of the PV product; returns this lane's sum of the rounded weights (the row
-        // sum is taken over the weights the PV product uses)
-        auto weights = [&](const f32x16 &sc, bf16x8 (&pf)[2]) -> float {
-            float l_blk = 0.f;
+        // as the B operand of the PV product
+        auto weights = [&](const f32x16 &sc, bf16x8 (&pf)[2]) {
 #pragma unroll
             for (int v = 0; v < 16; v += 2) {
-                bf16x2 pp;
-                pp[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], c, -m));
-                pp[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v + 1], c, -m));
-                l_blk = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_blk, false);
-                pf[v / 8][v % 8] = pp[0];
-                pf[v / 8][v % 8 + 1] = pp[1];
+                pf[v / 8][v % 8] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], c, -m));
+                pf[v / 8][v % 8 + 1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[v + 1], c, -m));
             }
-            return l_blk;
+        };
+        // Is one of the lane's 16 weights 2 or more (or infinite, or not a number)?  Those are the bf16 patterns with
+        // the top exponent bit set; weights are not negative.
+        auto weights_out_of_range = [&](const bf16x8 (&pf)[2]) -> bool {
+            const u32x4 a = __builtin_bit_cast(u32x4, pf[0]), b = __builtin_bit_cast(u32x4, pf[1]);
+            const uint32_t any = (a[0] | a[1] | a[2]) | (a[3] | b[0] | b[1]) | (b[2] | b[3]);
+            return (any & 0x40004000u) != 0;
+        };
+        // This lane's sum of the rounded weights (the row sum is taken over the weights the PV product uses):
+        // plain VALU additions, which go out between the matrix instructions of the PV product.
+        auto weight_sum = [&](const bf16x8 &pfj) -> float {       // of the 8 weights of one PV step
+            const u32x4 a = __builtin_bit_cast(u32x4, pfj);
+            float lo = 0.f, hi = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo += __builtin_bit_cast(float, a[i] << 16);
+                hi += __builtin_bit_cast(float, a[i] & 0xffff0000u);
+            }
+            return lo + hi;
         };
         // The second half of a block: scores of the next block (its K fragments
         // are in kf; discarded after the last block) on the matrix cores, interleaved with
@@ -706,11 +718,14 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // v_off: where in LDS the block's V fragments are, if they are still to be read (spread between the score
         // products, behind the K fragments those wait for); a negative value: vf holds them already.
         // at_point(1), at_point(2): two of the places where a wavefront may issue the next stage's loads.
-        auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, s16x8 (&vf)[2 * DBLK], auto v_off, auto &&at_point) {
-            constexpr int V_OFF = decltype(v_off)::value;
+        // vn_off: where the V fragments of the block after this one are, if they are to be read into vn between the
+        // matrix instructions of this block's PV product.
+        auto softmax_pv = [&](f32x16 &s_cur, f32x16 &s_next, s16x8 (&vf)[2 * DBLK], auto v_off, auto &&at_point, s16x8 (&vn)[2 * DBLK],
+                              auto vn_off) {
+            constexpr int V_OFF = decltype(v_off)::value, VN_OFF = decltype(vn_off)::value;
             bf16x8 pf[2];
-            float l_blk;
-            if constexpr (KS == 1) {
+            constexpr bool PHASED = KS == 1;
+            if constexpr (PHASED) {
                 // Four-wavefront workgroups run two to a compute unit, so the two wavefronts of a SIMD belong
                 // to different workgroups and are not held in step by a common barrier.  Here the block has a
                 // VALU phase (the weights) and an MFMA phase at raised wavefront priority: one wavefront's
@@ -719,7 +734,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 // eight-wavefront workgroups, whose SIMD partners meet at every barrier, no gain).
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (V_OFF >= 0) load_v(vf, V_OFF);
-                l_blk = weights(s_cur, pf);
+                weights(s_cur, pf);
                 __builtin_amdgcn_sched_barrier(0);
                 at_point(1);
                 __builtin_amdgcn_s_setprio(3);
@@ -729,7 +744,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 __builtin_amdgcn_sched_barrier(0);
                 s_next = qk(kf);
                 if constexpr (V_OFF >= 0) load_v(vf, V_OFF);
-                l_blk = weights(s_cur, pf);
+                weights(s_cur, pf);
                 // wanted order: one MFMA of the score chain, then its share of the LDS reads and of the VALU
                 // operations (exponentials are a class of their own), 8 times
 #pragma unroll
@@ -738,21 +753,21 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     if constexpr (V_OFF >= 0) __builtin_amdgcn_sched_group_barrier(0x100, 4 * DBLK / KSTEPS, 0);
                     __builtin_amdgcn_sched_group_barrier(0x002, 16 / KSTEPS, 0);
                     __builtin_amdgcn_sched_group_barrier(0x400, 16 / KSTEPS, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 16 / KSTEPS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8 / KSTEPS, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 // (the weights are needed here: computed in front of the branch below, inside the region the
                 // order above applies to, not moved behind it)
-                asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(l_blk));
+                asm volatile("" : "+v"(pf[0]), "+v"(pf[1]));
                 at_point(1);
             }
             // m is only a reference point, not the exact row maximum: any value keeps the result exact
-            // as long as the weights stay in range.  Only when a lane's weights of this block sum to
-            // more than 2^16 (or overflowed: first block, or scores far above anything seen before) is
-            // m raised to the true maximum, O and the row sum rescaled in place, and the weights
-            // recomputed.  The two half-waves of a row take the same decision.  (In the
-            // phased order the vote sits behind the score MFMAs, where its operands are long there.)
-            if (__builtin_amdgcn_ballot_w64(!(l_blk <= 65536.0f)) != 0) {
+            // as long as the weights stay in range.  Only when one of a lane's weights of this block reaches 2
+            // (or overflowed: first block, or scores far above anything seen before) is m raised to
+            // the true maximum, O and the row sum rescaled in place, and the weights recomputed.  The
+            // two half-waves of a row take the same decision.  (In the phased order the vote sits
+            // behind the score MFMAs, where its operands are long there.)
+            if (__builtin_amdgcn_ballot_w64(weights_out_of_range(pf)) != 0) {
                 float mx = s_cur[0] * c;
 #pragma unroll
                 for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v] * c);
@@ -768,18 +783,32 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 for (int i = 0; i < DBLK; ++i)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(o[i][v]) : "v"(alpha));
-                l_blk = weights(s_cur, pf);
+                weights(s_cur, pf);
             }
-            lsum += l_blk;
-            // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7.
+            // O^T += V^T P^T.  Step j contracts the 16 keys held in accumulator elements 8j..8j+7.  The row sum's
+            // additions are spread between the matrix instructions.
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
+                if constexpr (!PHASED) __builtin_amdgcn_sched_barrier(0);
+                float wsum = weight_sum(pf[j]);
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j * DBLK + db]), pf[j], o[db], 0, 0, 0);
-                if (KS != 1 && j == 0) at_point(2);
+                if constexpr (VN_OFF >= 0) load_v_half(vn, VN_OFF, j);
+                if constexpr (!PHASED) {
+#pragma unroll
+                    for (int db = 0; db < DBLK; ++db) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if constexpr (VN_OFF >= 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 18 / DBLK + 1, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                asm volatile("" : "+v"(wsum));           // computed here, between the matrix instructions, not later
+                lsum += wsum;
+                if (!PHASED && j == 0) at_point(2);
             }
-            if constexpr (KS == 1) {
+            if constexpr (PHASED) {
                 __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
                 at_point(2);
@@ -824,7 +853,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     if (key > bound) s_cur[v] = masked;
                 }
             }
-            softmax_pv(s_cur, s_next, vf, std::integral_constant<int, -1>(), issue_pending);
+            softmax_pv(s_cur, s_next, vf, std::integral_constant<int, -1>(), issue_pending, vf, std::integral_constant<int, -1>());
             return have_next;
         };
         // ---- steady state.  Most of a long key range is whole stages of cached keys: both of the wavefront's
@@ -835,14 +864,14 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // blocks below take over with the same state wherever one of the conditions does not hold.
         // step<B>: on entry stage `it` is in buffer B, s_a holds the scores of its first block and the loads of stage
         // it + 1 are issued; on exit the same holds for stage it + 1 in buffer 1 - B.
+        const int steady_end = min(n_stages, L / STAGE);       // stages before it are whole stages of cached keys
         f32x16 s_a = qk(kf), s_b;
         auto steady_step = [&](auto buffer) {
             constexpr int cur = decltype(buffer)::value * (int)STAGE_BYTES, nxt = (int)STAGE_BYTES - cur;
-            s16x8 vf[2 * DBLK];
+            s16x8 vf[2 * DBLK], vf2[2 * DBLK];
             load_k(kf, cur + BLOCK_BYTES);
-            softmax_pv(s_a, s_b, vf, std::integral_constant<int, cur>(), [](int) {});
-            load_v(vf, cur + BLOCK_BYTES);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // V fragments are out of LDS: the stage may be left
+            softmax_pv(s_a, s_b, vf, std::integral_constant<int, cur>(), [](int) {}, vf2, std::integral_constant<int, cur + BLOCK_BYTES>());
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the second block's V fragments are out of LDS: the stage may be left
             ++it;
             wait_vm<0>();
             __syncthreads();
@@ -862,10 +891,9 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 }
             };
             loads_at(0);
-            softmax_pv(s_b, s_a, vf, std::integral_constant<int, -1>(), loads_at);
+            softmax_pv(s_b, s_a, vf2, std::integral_constant<int, -1>(), loads_at, vf2, std::integral_constant<int, -1>());
             loads_at(3);
         };
-        const int steady_end = min(n_stages, L / STAGE);       // stages before it are whole stages of cached keys
         for (;;) {
             if (kb == 0 && nblk == NKB && buf_of(it) == 0 && it + 3 < steady_end && stashed && (ho.unit < 0 || ho.announced)) {
                 if (pend) {

@@ -338,6 +338,24 @@ __device__ __forceinline__ char *piece_scratch(const AttnParams &p, int grp, int
     return p.scratch + unit * unit_bytes<D>();
 }
 
+// The output rows of a wavefront.  Lane (l32, half) holds for its row and every (db, q4) the four values
+// d = 32 db + 8 q4 + 4 half + 0..3 (8 bytes); chunk(db, q4) returns them rounded.  The two half-waves exchange what
+// they hold of two neighbouring q4 (v_permlane32_swap: the upper half of the first register with the lower half of
+// the second), after which the lower half-wave has the 8 values of the even q4 and the upper one those of the odd
+// q4: 16 bytes per lane and store, half as many stores as without the exchange.
+template <int D, typename F>
+__device__ __forceinline__ void store_out_rows(uint16_t *orow, int half, F &&chunk)
+{
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4 += 2) {
+            uint2 a = chunk(db, q4), b = chunk(db, q4 + 1);
+            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %2\n\tv_permlane32_swap_b32 %1, %3\n\ts_nop 1" : "+v"(a.x), "+v"(a.y), "+v"(b.x), "+v"(b.y));
+            *reinterpret_cast<uint4 *>(orow + db * 32 + (q4 + half) * 8) = make_uint4(a.x, a.y, b.x, b.y);
+        }
+}
+
 // All pieces of a tile are there: merge them, normalise, write the rows.  `mine` is the piece this
 // wavefront has not written to the scratch memory: its O is in LDS at `own` (parked there so that the
 // merge holds two copies of O in registers, not three), its m and row sum in (m, l); -1 when all
@@ -389,15 +407,12 @@ __device__ __forceinline__ void finish_tile(const AttnParams &p, int grp, int wf
     if (!row_ok) return;
     const float inv = __builtin_amdgcn_rcpf(lacc);
     uint16_t *orow = p.out + ((size_t)row * p.Hq + head) * D;     // (worked out here: a pointer kept across the loop above costs two registers)
+    store_out_rows<D>(orow, half, [&](int db, int q4) {
+        bf16x4 w;
 #pragma unroll
-    for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[db][q4 * 4 + e] * inv);
-            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
-        }
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[db][q4 * 4 + e] * inv);
+        return __builtin_bit_cast(uint2, w);
+    });
 }
 
 // The same for a tile of two pieces, of which this wavefront holds one (`piece`) in registers: one round trip for the
@@ -420,19 +435,16 @@ __device__ __forceinline__ void finish_pair(const AttnParams &p, int grp, int wf
     if (!row_ok) return;
     const float inv = __builtin_amdgcn_rcpf(l);
     uint16_t *orow = p.out + ((size_t)row * p.Hq + head) * D;
+    store_out_rows<D>(orow, half, [&](int db, int q4) {
+        bf16x4 w;
 #pragma unroll
-    for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
-                const float r = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
-                w[e] = (__bf16)(r * inv);
-            }
-            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half) = __builtin_bit_cast(uint2, w);
+        for (int e = 0; e < 4; ++e) {
+            const float y = o[db][q4 * 4 + e], z = x[db * 4 + q4][e];
+            const float r = piece == 0 ? __builtin_fmaf(z, w_oth, y * w_own) : __builtin_fmaf(y, w_own, z * w_oth);
+            w[e] = (__bf16)(r * inv);
         }
+        return __builtin_bit_cast(uint2, w);
+    });
 }
 
 // What carries over from one job of a workgroup to the next.
@@ -1062,15 +1074,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     if (!row_ok_e) return;
     const float inv = __builtin_amdgcn_rcpf(ltot);
     uint16_t *orow = pe.out + ((size_t)(J.seg_cu + t_e) * pe.Hq + head) * D;
+    store_out_rows<D>(orow, half_e, [&](int db, int q4) {
+        bf16x4 w;
 #pragma unroll
-    for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
-            *reinterpret_cast<uint2 *>(orow + db * 32 + q4 * 8 + 4 * half_e) = __builtin_bit_cast(uint2, w);
-        }
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][q4 * 4 + e] * inv);
+        return __builtin_bit_cast(uint2, w);
+    });
     TETRI_MARK((first_job ? 0 : 12) + 6);
 }
 

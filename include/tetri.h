@@ -364,14 +364,20 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  *   "attn_variant"      0 = the library chooses the workgroup size (8 wavefronts; 4, two workgroups to a
  *                       compute unit, when a full chunk alone gives two workgroups per compute unit), 1 / 2 =
  *                       4- / 8-wavefront workgroups;
- *   "split_keys"        1 (default) = a launch with fewer than two row tiles per compute unit lays the stages
- *                       (64 or 128 keys each) of all row tiles of a head group end to end and gives every
- *                       workgroup of the group an equal range of them; tiles shared by several workgroups are
- *                       finished from partial results in the handle's scratch memory; 0 = always one
- *                       workgroup per row tile;
- *   "stream_wgs"        workgroups per head group of such a launch (default 0: as many as the device has
- *                       compute units for); a value of 1..255 also forces this mode for launches of any size
- *                       with at most 64 segments;
+ *   "split_keys"        1 (default) = a launch with fewer than two row tiles per compute unit divides the key
+ *                       ranges of its tiles among more workgroups than it has tiles.  If the tiles and one helper
+ *                       workgroup per two tiles fit the compute units, every tile with a long key range hands the
+ *                       tail of it to its helper; otherwise (and only for chunks whose segments have 256 rows or
+ *                       more on average, and at most 64 segments) the stages (64 or 128 keys each) of all row
+ *                       tiles of a head group are laid end to end and every workgroup of the group gets an equal
+ *                       range of them.  Tiles shared by several workgroups are finished from partial results in
+ *                       the handle's scratch memory (see tetri_create).  0 = always one workgroup per row tile;
+ *   "split_min_stages"  tails: key ranges of fewer stages than this are not divided (default 8; at least 2);
+ *   "split_bias_stages" tails: stages a tile keeps before the rest is shared (default 5; not negative);
+ *   "split_share_q8"    tails: share of that rest the helper takes, in 1/256 (default 85; 1..128);
+ *   "stream_wgs"        workgroups per head group when the stages are laid end to end (default 0: as many as
+ *                       the device has compute units for); a value of 1..255 also forces that division for
+ *                       launches of any size with at most 64 segments;
  *   "decode_parts"      workgroups that share the keys of one (request, kv head) in tetri_decode_attn
  *                       (default 0: chosen from num_reqs and max_ctx_len);
  *   "transfer_slabs"    (K / V, head) slabs one workgroup of tetri_kv_export / tetri_kv_import moves

@@ -373,7 +373,7 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
  *                       range of them.  Tiles shared by several workgroups are finished from partial results in
  *                       the handle's scratch memory (see tetri_create).  0 = always one workgroup per row tile;
  *   "split_min_stages"  tails: key ranges of fewer stages than this are not divided (default 8; at least 2);
- *   "split_bias_stages" tails: stages a tile keeps before the rest is shared (default 5; not negative);
+ *   "split_bias_stages" tails: stages a tile keeps before the rest is shared (default 6; not negative);
  *   "split_share_q8"    tails: share of that rest the helper takes, in 1/256 (default 85; 1..128);
  *   "stream_wgs"        workgroups per head group when the stages are laid end to end (default 0: as many as
  *                       the device has compute units for); a value of 1..255 also forces that division for

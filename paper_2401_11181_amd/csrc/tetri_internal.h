@@ -13,7 +13,7 @@ struct tetri_ctx {
     int split_keys = 1;     // 1 = launches with fewer than two row tiles per CU divide the stages of every head group evenly over the CUs
     int stream_wgs = 0;     // workgroups per head group of such a launch (0: as many as the device has CUs for); > 0 forces the mode
     int split_min_stages = 8;   // tail mode: the shortest key range that hands its tail to a helper workgroup
-    int split_bias_stages = 5;  // a helper's overhead, in stages (see the kernel)
+    int split_bias_stages = 6;  // a helper's overhead, in stages (see the kernel)
     int split_share_q8 = 85;    // the share of the remaining stages a tile hands over, in 1/256 (a third)
     int decode_parts = 0;       // key parts per (request, kv head) of the decode kernel (0: the library chooses)
     int transfer_slabs = 0;     // (K / V, head) slabs per workgroup of the export / import kernels (0: the library chooses)

@@ -10,10 +10,11 @@ chunk's attention and its KV append (TetriInfer Sec. 3.3.3: prefill one ChunkSiz
 HBM before the timed region.  Prints ONE JSON line.
 
 `value` = algorithmic attention flops of a step / step time with a COLD cache: consecutive steps rotate over
-independent copies of every buffer (inputs, output, page pool), so that more than twice the 256 MB last-level
-cache is touched before a buffer comes round again.  `warm_cache` is the same step on one set of buffers, back
-to back.  `roofline` is the attention kernel alone, its launch durations measured with HIP events (on the
-launch stream) around graph-replayed groups of launches that rotate over the same buffer sets.
+independent copies of every buffer the caller owns (inputs, output, page pool, metadata; one library handle), so
+that more than twice the 256 MB last-level cache is touched before a buffer comes round again.  `warm_cache` is
+the same step on one set of buffers, back to back.  `roofline` is the attention kernel alone, its launch durations
+measured with HIP events (on the launch stream) around graph-replayed groups of launches that rotate over the same
+buffer sets.
 
 Beside the contract's fields the line carries stand-alone measurements taken after the timed region:
 `per_chunk`, `roofline.per_chunk_bound_frac` (each chunk against the roofline that binds it:
@@ -243,11 +244,12 @@ def main():
     tables = synth.place_pages(w)
     fused = not args.two_launches
 
-    def new_pipe(export=None):
+    def new_pipe(export=None, handle=None):
         pp = PrefillPipeline(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                              w.num_pages, tables, w.scale, device=dev, page_size=w.page_size,
-                             use_graph=(args.mode == "graph"), fused=fused, export=export)
-        set_options(pp, args)
+                             use_graph=(args.mode == "graph"), fused=fused, export=export, handle=handle)
+        if handle is None:
+            set_options(pp, args)
         return pp
 
     pipe = new_pipe(args.export)
@@ -290,7 +292,7 @@ def main():
         n_sets = 1
     sets, keep = [pipe], []
     for _ in range(n_sets - 1):
-        pp = new_pipe()
+        pp = new_pipe(handle=pipe.handle)           # one handle: the library's own scratch memory is the same in every step
         bufs = (q.clone(), k.clone(), v.clone(), pool.clone(), torch.zeros_like(out))
         pp.bind(*bufs)
         keep.append(bufs)

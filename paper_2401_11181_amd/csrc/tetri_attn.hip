@@ -868,15 +868,19 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             softmax_pv(s_cur, s_next, vf, std::integral_constant<int, -1>(), issue_pending, vf, std::integral_constant<int, -1>());
             return have_next;
         };
-        // ---- steady state.  Most of a long key range is whole stages of cached keys: both of the wavefront's
-        // blocks exist, nothing is masked, all 16 rows the wavefront loads exist, and after the job's first
-        // stages no announcement is pending.  Two such stages are one trip of a loop in which all of that is
-        // known: the stage buffers alternate at compile time (LDS offsets are instruction immediates), a stage's
-        // loads are its page base plus constants, and no block asks what kind of block it is.  The general
-        // blocks below take over with the same state wherever one of the conditions does not hold.
+        // ---- steady state.  Most of a key range is whole stages in which both of the wavefront's blocks exist and
+        // nothing is masked: the whole stages of cached keys and, if the cached keys end on a stage boundary, the
+        // stages of new keys that lie entirely in front of the wavefront's rows.  After the job's first stages no
+        // announcement is pending either.  Two such stages are one trip of a loop in which all of that is
+        // known: the stage buffers alternate at compile time (LDS offsets are instruction immediates) and no block
+        // asks what kind of block it is; the loads of a whole stage of cached keys are its page base plus
+        // constants (any other stage's loads are described the general way).  The general blocks below take
+        // over with the same state wherever one of the conditions does not hold: the diagonal, a ragged end.
         // step<B>: on entry stage `it` is in buffer B, s_a holds the scores of its first block and the loads of stage
         // it + 1 are issued; on exit the same holds for stage it + 1 in buffer 1 - B.
-        const int steady_end = min(n_stages, L / STAGE);       // stages before it are whole stages of cached keys
+        const int ctx_whole = L / STAGE;                       // stages before it are whole stages of cached keys
+        // (new key j is visible to local row t >= j: stage x of new keys is unmasked for rows from tw0 on if (x + 1) * STAGE <= tw0 + 1)
+        const int steady_end = min(n_stages, L % STAGE == 0 ? ctx_whole + (tw0 + 1) / STAGE : ctx_whole);
         f32x16 s_a = qk(kf), s_b;
         auto steady_step = [&](auto buffer) {
             constexpr int cur = decltype(buffer)::value * (int)STAGE_BYTES, nxt = (int)STAGE_BYTES - cur;
@@ -891,15 +895,20 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             const int pg = page;                                 // of stage it + 1, which goes where stage it - 1 was
             page = load_stage_page<KS>(bt_row, ws.max_blocks, it + 2, wave);
             auto loads_at = [&](int point) {
-                if (load_point == point) {
+                if (load_point == point && it + 1 < n_stages) {
                     StageLoads st;
-                    st.kb = ws.pool_k + (size_t)pg * ws.page_bytes;
-                    st.vb = st.kb + ws.v_delta;
-                    st.step = 0;
-                    st.kdst = smem_lds + cur + wave * (16 * D * 2);
-                    st.ko = lo.k_ctx;
-                    st.vo = lo.v_ctx;
-                    issue_stage_loads<D, KS>(st, true);
+                    if (it + 1 < ctx_whole) {
+                        st.kb = ws.pool_k + (size_t)pg * ws.page_bytes;
+                        st.vb = st.kb + ws.v_delta;
+                        st.step = 0;
+                        st.kdst = smem_lds + cur + wave * (16 * D * 2);
+                        st.ko = lo.k_ctx;
+                        st.vo = lo.v_ctx;
+                        issue_stage_loads<D, KS>(st, true);
+                    } else {
+                        const bool full = describe_stage_loads<D, KS>(src, ws, lo, pg, it + 1, wave, new_row_bytes, smem_lds + cur, st);
+                        issue_stage_loads<D, KS>(st, full);
+                    }
                 }
             };
             loads_at(0);
@@ -907,15 +916,17 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             loads_at(3);
         };
         for (;;) {
-            if (kb == 0 && nblk == NKB && buf_of(it) == 0 && it + 3 < steady_end && stashed && (ho.unit < 0 || ho.announced)) {
+            // (a step enters stage it + 1: that one has to be a steady stage)
+            if (kb == 0 && nblk == NKB && buf_of(it) == 0 && it + 1 < steady_end && stashed && (ho.unit < 0 || ho.announced)) {
                 if (pend) {
                     issue_stage_loads<D, KS>(sl, true);
                     pend = false;
                 }
-                do {
+                while (it + 2 < steady_end) {
                     steady_step(std::integral_constant<int, 0>());
                     steady_step(std::integral_constant<int, 1>());
-                } while (it + 3 < steady_end);
+                }
+                if (it + 1 < steady_end) steady_step(std::integral_constant<int, 0>());
             }
             if (!block(s_a, s_b)) break;
             if (!block(s_b, s_a)) break;

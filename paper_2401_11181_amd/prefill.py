@@ -104,7 +104,7 @@ class PrefillPipeline:
     RING = 4    # pinned staging buffers in flight
 
     def __init__(self, prompt_lens, order, chunk_size, num_q_heads, num_kv_heads, head_dim, num_pages,
-                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False, fused=True, export=None):
+                 req_block_tables, scale, device="cuda:0", page_size=16, use_graph=False, fused=True, export=None, handle=None):
         self.device = torch.device(device)
         self.C, self.Hq, self.Hkv, self.D = chunk_size, num_q_heads, num_kv_heads, head_dim
         self.scale = float(scale)
@@ -132,8 +132,9 @@ class PrefillPipeline:
         self.host_plan(0)
         self.layout = [tuple(int(x) for x in row) for row in self.layout_np[:self.n_chunks]]
         max_segs = max([1] + [l[3] for l in self.layout])
-        self.handle = tetri.Tetri(num_q_heads, num_kv_heads, head_dim, chunk_size, num_pages, self.max_blocks,
-                                  max_segs, page_size=page_size)
+        # (several pipelines of one shape may share a handle, as long as their launches do not overlap)
+        self.handle = handle or tetri.Tetri(num_q_heads, num_kv_heads, head_dim, chunk_size, num_pages, self.max_blocks,
+                                            max_segs, page_size=page_size)
         self.events = [torch.cuda.Event() for _ in range(self.RING)]
         self.used = [False] * self.RING
         self.graph = None

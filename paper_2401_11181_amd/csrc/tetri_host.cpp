@@ -402,22 +402,24 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     const int groups = p.Hq / p.hpw;
     const int cus = std::max(h->num_cus, 1);
     // Workgroup size of the shared-tile kernel.  A full chunk has at least C / (rows of a tile) tiles per head
-    // group; when that alone gives two workgroups per compute unit, four-wavefront workgroups (two to a CU, their
-    // barriers independent of each other) run the block loop 4-15 % faster than eight-wavefront ones; on smaller
+    // group; when that alone gives five workgroups per four compute units or more, four-wavefront workgroups (two
+    // to a CU, their barriers independent of each other), one per tile, do best: with two per CU everywhere they run
+    // the block loop 4-15 % faster than eight-wavefront ones, and at 1.25 per CU (ChunkSize 1024 at 40 heads)
+    // still 4 % faster than eight-wavefront workgroups that divide the stages of a head among them.  On smaller
     // launches the eight-wavefront workgroup, which puts twice the wavefronts on its tile's CU, is the better one.
     int key_parts = h->attn_variant == 1 ? 1 : 2;
-    if (h->attn_variant == 0 && h->stream_wgs == 0 && (int64_t)(p.C / (32 * p.rb)) * groups >= 2 * (int64_t)cus) key_parts = 1;
+    if (h->attn_variant == 0 && h->stream_wgs == 0 && (int64_t)(p.C / (32 * p.rb)) * groups * 4 >= 5 * (int64_t)cus) key_parts = 1;
     p.tiles = tile_bound(p.C, p.S, 32 * p.rb);
     p.gpx = (groups + 7) / 8;
     // How the work of a head group is handed out (see the kernel):
     //  - tail mode: a launch whose row tiles would occupy at most two thirds of the compute units gets one more
     //    workgroup per two tiles, which takes the tails of their key ranges; all tiles of a head start together and
     //    walk the keys side by side, so K and V come out of L2 for all but the first of them;
-    //  - stream mode: a launch with more tiles than that but fewer than two per compute unit gives every head
+    //  - stream mode: a launch with more tiles than that but fewer than five per four compute units gives every head
     //    group G workgroups that share the stages of all its tiles evenly (measured: better than a second, mostly
-    //    empty round of workgroups, worse than tail mode where that applies: workgroups of a head then read
-    //    different parts of K and V at any one time);
-    //  - tile mode: one workgroup per row tile.
+    //    empty round of eight-wavefront workgroups, worse than tail mode where that applies: workgroups of a head
+    //    then read different parts of K and V at any one time);
+    //  - tile mode: one workgroup per row tile (launches with more tiles than that: four-wavefront workgroups).
     // The divisions are worked out on the device from the segment lengths; the host only has to know that
     // the numbers fit: scratch memory and arrival counters for every (tile, slot) resp. (workgroup, slot), and for
     // stream mode at most 64 segments (one lane each) and positions times G in 31 bits.
@@ -433,7 +435,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
             p.helpers = helpers;
         // (segments of under 256 rows on average are a batch of short prompts: a handful of stages per tile, which
         // the division would only cut into smaller pieces)
-        else if ((int64_t)p.tiles * groups < 2 * (int64_t)cus && (int64_t)p.C >= 256 * (int64_t)p.S)
+        else if ((key_parts == 2 || h->attn_variant == 1) && (int64_t)p.tiles * groups < 2 * (int64_t)cus && (int64_t)p.C >= 256 * (int64_t)p.S)
             G = std::min(255, (cus - (kv_pages_w ? 8 : 0)) / groups);
     }
     const int stage = 64 * key_parts;

@@ -59,12 +59,14 @@ def aimed_rows(segs, n_samples, rng):
     return np.asarray(rows, dtype=np.int32)
 
 
-def run_sampled(oracle, w, check_chunks, n_samples, seed, dense_chunks=(), dense_heads=()):
+def run_sampled(oracle, w, check_chunks, n_samples, seed, dense_chunks=(), dense_heads=(), options=None):
     """Run the whole workload on the GPU, one fused launch per chunk as bench.py does; check sampled outputs
     of the given chunks (every row of `dense_heads` in `dense_chunks`) and the pool."""
     qs, ks, vs, tables = gc.workload_tensors(w)
     sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
                           w.num_pages, tables, device=DEV, page_size=w.page_size)
+    for key, value in (options or {}).items():
+        sess.handle.tetri_set_option(key, value)
     plan = opacker.pack_chunks(w.prompt_lens, w.order, w.chunk_size)
     assert [sess.chunk_segments(c) for c in range(sess.n_chunks)] == [list(c) for c in plan]
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
@@ -142,14 +144,15 @@ def test_gqa_config_sampled(oracle):
                       dense_chunks=dense, dense_heads=(1, 10, 19, 28)))
 
 
-@pytest.mark.parametrize("chunk_size", [1024, 4096])
-def test_large_chunk_sizes_sampled(oracle, chunk_size):
+@pytest.mark.parametrize("chunk_size,stream_wgs", [(1024, 0), (1024, 6), (4096, 0)], ids=["1024", "1024-stream6", "4096"])
+def test_large_chunk_sizes_sampled(oracle, chunk_size, stream_wgs):
     """One 8192-token prompt on the 13B head shape (40 x 128) with ChunkSize 1024 and 4096: launches with more row
-    tiles than two thirds of the compute units.  With 1024 the library gives every head its share of workgroups
-    and divides the head's stages evenly among them (tiles of many pieces); with 4096 there are two whole tiles per
-    compute unit and four-wavefront workgroups."""
+    tiles than compute units, which the library runs with four-wavefront workgroups, one per tile (1.25 and 5 per
+    compute unit).  With `stream_wgs` 6 the ChunkSize-1024 launches instead give every head six eight-wavefront
+    workgroups that divide the head's stages evenly among them (tiles of many pieces), at full size."""
     base = synth.workload("opt13b")
     w = dataclasses.replace(base, name="opt13b-len8192-chunk%d" % chunk_size, prompt_lens=[8192], order=[0],
                             chunk_size=chunk_size, num_pages=8192 // base.page_size + 64, seed=3000 + chunk_size)
     n_chunks = 8192 // chunk_size
-    print(run_sampled(oracle, w, check_chunks=sorted({0, 1, n_chunks // 2, n_chunks - 1}), n_samples=96, seed=6))
+    opts = {"stream_wgs": stream_wgs} if stream_wgs else {}
+    print(run_sampled(oracle, w, check_chunks=sorted({0, 1, n_chunks // 2, n_chunks - 1}), n_samples=96, seed=6, options=opts))

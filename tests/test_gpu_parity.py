@@ -56,6 +56,9 @@ CASES = {
     "gqa3": ([150, 40], 64, 6, 2, 64),
     "single-token-prompt": ([1], 16, 2, 1, 128),
     "many-tiles": ([700], 512, 2, 2, 128),
+    # cached keys end on a stage boundary: whole stages of new keys in front of the diagonal take the kernel's steady loop
+    "aligned-chunks": ([1536], 512, 2, 2, 128),
+    "aligned-chunks-d64": ([1100], 512, 4, 2, 64),
 }
 
 

@@ -362,9 +362,9 @@ TETRI_API tetri_status tetri_validate_chunk(tetri_ctx *ctx, const int32_t *block
 /*
  * Kernel-variant selection for measurements and tests.  Known keys:
  *   "attn_variant"      0 = the library chooses the workgroup size (8 wavefronts; 4, two workgroups to a
- *                       compute unit, when a full chunk alone gives two workgroups per compute unit), 1 / 2 =
- *                       4- / 8-wavefront workgroups;
- *   "split_keys"        1 (default) = a launch with fewer than two row tiles per compute unit divides the key
+ *                       compute unit, when a full chunk alone gives five row tiles per four compute units or
+ *                       more), 1 / 2 = 4- / 8-wavefront workgroups;
+ *   "split_keys"        1 (default) = a launch with fewer than five row tiles per four compute units divides the key
  *                       ranges of its tiles among more workgroups than it has tiles.  If the tiles and one helper
  *                       workgroup per two tiles fit the compute units, every tile with a long key range hands the
  *                       tail of it to its helper; otherwise (and only for chunks whose segments have 256 rows or

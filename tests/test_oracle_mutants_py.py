@@ -1,4 +1,5 @@
-"""Planted mistakes in the numpy oracles (KV transfer, decode iteration) must be caught by their pins.
+"""Planted mistakes in the numpy oracles (KV transfer, decode iteration, FP8 codes, chunked prefill over a cache of
+codes) must be caught by their pins.
 
 Each mutant is the oracle's source with one plausible slip; it is executed as a module of its own,
 swapped in for the real one inside the pin-test module, and every pin is run against it: at least one
@@ -12,11 +13,42 @@ import pytest
 import test_oracle_decode as decode_pins
 import test_oracle_fp8 as fp8_pins
 import test_oracle_kv_transfer as transfer_pins
-from oracle import decode, fp8, kv_transfer
+import test_oracle_prefill_fp8 as prefill_fp8_pins
+from oracle import decode, fp8, kv_transfer, prefill_fp8
 
 TRANSFER_SRC = inspect.getsource(kv_transfer)
 DECODE_SRC = inspect.getsource(decode)
 FP8_SRC = inspect.getsource(fp8)
+PREFILL_FP8_SRC = inspect.getsource(prefill_fp8).replace("from . import fp8", "from oracle import fp8")
+
+PREFILL_FP8_MUTANTS = {
+    "scale-on-own-keys": ("    keys[L:] = k_new[a:b, kh, :]", "    keys[L:] = k_new[a:b, kh, :] * 0.5"),
+    "scale-on-own-values": ("    vals[L:] = v_new[a:b, kh, :]", "    vals[L:] = v_new[a:b, kh, :] * 0.5"),
+    "scales-swapped": ("    k_vals = fp8.dequantize(kv_codes[:, 0], k_scale)\n    v_vals = fp8.dequantize(kv_codes[:, 1], v_scale)",
+                       "    k_vals = fp8.dequantize(kv_codes[:, 0], v_scale)\n    v_vals = fp8.dequantize(kv_codes[:, 1], k_scale)"),
+    "values-from-keys": ("        vals[j] = v_vals[page, kh, j % P, :]", "        vals[j] = k_vals[page, kh, j % P, :]"),
+    "slot-index": ("        keys[j] = k_vals[page, kh, j % P, :]", "        keys[j] = k_vals[page, kh, j // P % P, :]"),
+    "table-row": ("            keys, vals = _segment_kv(k_new, v_new, k_vals, v_vals, block_table[s], L, a, b, kh, P)",
+                  "            keys, vals = _segment_kv(k_new, v_new, k_vals, v_vals, block_table[0], L, a, b, kh, P)"),
+    "own-position-masked": ("                    out[a + t, h] = _one_row(q[a + t, h], keys, vals, L + t + 1, scale)",
+                            "                    out[a + t, h] = _one_row(q[a + t, h], keys, vals, max(L + t, 1), scale)"),
+    "sees-the-future": ("                    out[a + t, h] = _one_row(q[a + t, h], keys, vals, L + t + 1, scale)",
+                        "                    out[a + t, h] = _one_row(q[a + t, h], keys, vals, L + (b - a), scale)"),
+    "gqa-mapping": ("            for h in range(kh * g, (kh + 1) * g):", "            for h in range(kh, Hq, Hkv):"),
+    "drop-scale": ("    s = scale * (keys[:visible] @ qrow)", "    s = keys[:visible] @ qrow"),
+    "samples-forget-k-scale": ("            keys = np.concatenate([table[kc] * ks, k_new[a:b, kh, :]], axis=0)",
+                               "            keys = np.concatenate([table[kc], k_new[a:b, kh, :]], axis=0)"),
+    "samples-row-offset": ("        out[i] = _one_row(q[r, h], keys, vals, L + (r - a) + 1, scale)",
+                           "        out[i] = _one_row(q[r, h], keys, vals, L + r + 1, scale)"),
+    "append-slot": ("            kv_codes[page, 0, :, pos % P, :] = fp8.quantize(np.asarray(k_new[a + t], dtype=np.float32), k_scale)",
+                    "            kv_codes[page, 0, :, t % P, :] = fp8.quantize(np.asarray(k_new[a + t], dtype=np.float32), k_scale)"),
+    "append-v-under-k-scale": ("fp8.quantize(np.asarray(v_new[a + t], dtype=np.float32), v_scale)",
+                               "fp8.quantize(np.asarray(v_new[a + t], dtype=np.float32), k_scale)"),
+    "append-ignores-context": ("            pos = L + t\n            page = int(block_table[s][pos // P])\n            kv_codes[page, 0",
+                               "            pos = t\n            page = int(block_table[s][pos // P])\n            kv_codes[page, 0"),
+    "append-chunk-row": ("fp8.quantize(np.asarray(k_new[a + t], dtype=np.float32), k_scale)",
+                         "fp8.quantize(np.asarray(k_new[t], dtype=np.float32), k_scale)"),
+}
 
 FP8_MUTANTS = {
     "exponent-bias": ("            t[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)", "            t[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 8)"),
@@ -98,6 +130,8 @@ def test_every_mutation_site_exists():
         assert DECODE_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
     for name, (old, _new) in FP8_MUTANTS.items():
         assert FP8_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
+    for name, (old, _new) in PREFILL_FP8_MUTANTS.items():
+        assert PREFILL_FP8_SRC.count(old) == 1, "mutation site for %s not found exactly once" % name
 
 
 @pytest.mark.parametrize("name", sorted(TRANSFER_MUTANTS))
@@ -112,6 +146,13 @@ def test_decode_pins_catch_mutant(name, oracle):
     old, new = DECODE_MUTANTS[name]
     mutant = module_from(DECODE_SRC.replace(old, new), "decode_mutant_" + name.replace("-", "_"))
     assert run_pins(decode_pins, "decode", mutant, oracle), "no pin noticed the planted mistake '%s'" % name
+
+
+@pytest.mark.parametrize("name", sorted(PREFILL_FP8_MUTANTS))
+def test_prefill_fp8_pins_catch_mutant(name, oracle):
+    old, new = PREFILL_FP8_MUTANTS[name]
+    mutant = module_from(PREFILL_FP8_SRC.replace(old, new), "prefill_fp8_mutant_" + name.replace("-", "_"))
+    assert run_pins(prefill_fp8_pins, "prefill_fp8", mutant, oracle), "no pin noticed the planted mistake '%s'" % name
 
 
 def run_fp8_pins(mutant):
@@ -147,3 +188,4 @@ def test_unmutated_oracles_pass_the_same_calls(oracle):
     assert run_fp8_pins(fp8) == []
     assert run_pins(transfer_pins, "kv_transfer", kv_transfer, oracle) == []
     assert run_pins(decode_pins, "decode", decode, oracle) == []
+    assert run_pins(prefill_fp8_pins, "prefill_fp8", prefill_fp8, oracle) == []

@@ -349,6 +349,24 @@ TETRI_API tetri_status tetri_decode_attn_fp8(tetri_ctx *ctx, const void *q, cons
                                              float v_scale, int32_t append, void *out, void *stream);
 
 /*
+ * Chunked prefill over the FP8 cache (the same extension on the prefill side: an instance that keeps its cache in
+ * codes, e.g. a decode instance that takes over a prefill, Sec. 3.3.4 / 3.4, reads it without a 16-bit copy).
+ * tetri_chunk_prefill_attn over a pool of E4M3 codes in the format above: the cached K and V of a segment are
+ * value(code) * k_scale and value(code) * v_scale, the chunk's own rows k_new / v_new (bf16) enter unquantised.
+ * With append = 1 the codes of the chunk's rows (fl32(x * fl32(1 / scale)), clamped, rounded to nearest even) are
+ * also written to their slots of the pool, as tetri_chunk_prefill_attn_append does with the 16-bit values (the
+ * launch reads none of the slots it writes); with append = 0 the pool is only read.
+ *   kv_pages_fp8 device [num_pages][2][num_kv_heads][page_size][head_dim] bytes, 16-byte aligned; in/out with append = 1
+ * Every other argument, the scratch-memory rule and the errors as for tetri_chunk_prefill_attn;
+ * TETRI_ERR_INVALID_ARG also for scales that are not positive and finite and for append other than 0 / 1.
+ */
+TETRI_API tetri_status tetri_chunk_prefill_attn_fp8(tetri_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                                                    void *kv_pages_fp8, const int32_t *block_table,
+                                                    const int32_t *cu_chunk_q_lens, const int32_t *ctx_lens,
+                                                    int32_t num_segs, float scale, float k_scale, float v_scale,
+                                                    int32_t append, void *out, void *stream);
+
+/*
  * Debug check of device-resident chunk metadata.  Synchronises `stream`, copies the arrays to
  * the host and checks: cu[0] == 0, cu strictly increasing, cu[num_segs] <= chunk_size,
  * ctx_lens >= 0, every needed block-table entry in [0, num_pages), enough logical pages

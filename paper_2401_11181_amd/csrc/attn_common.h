@@ -200,6 +200,39 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// FP8 E4M3 cache: 16 codes (one 16-byte load) to 16 bf16 values, exactly (a code has four significant bits): lo
+// gets the values of codes 0..7, hi those of codes 8..15.
+__device__ __forceinline__ void codes_to_bf16(const u32x4 &raw, u32x4 &lo, u32x4 &hi)
+{
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        lo[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, false));
+        lo[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[w], 1.0f, true));
+        hi[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2 + w], 1.0f, false));
+        hi[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2 + w], 1.0f, true));
+    }
+}
+// ... and 8 bf16 values (16 bytes) to their 8 codes under fl32(1 / scale) = inv: fl32(x * inv) clamped to +-448,
+// rounded to nearest even by v_cvt_pk_fp8_f32.
+__device__ __forceinline__ uint2 bf16_to_codes(const u32x4 &v, float inv)
+{
+    uint32_t codes[2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t word = v[2 * w + e / 2];
+            const float x = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+            y[e] = __builtin_fminf(__builtin_fmaxf(x * inv, -448.0f), 448.0f);
+        }
+        int c = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+        c = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], c, true);
+        codes[w] = (uint32_t)c;
+    }
+    return make_uint2(codes[0], codes[1]);
+}
+
 // Everything a wavefront needs to know about where its workgroup's keys come from.
 struct KeySource {
     const uint16_t *pages, *k_new, *v_new;

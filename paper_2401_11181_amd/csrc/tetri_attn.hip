@@ -140,16 +140,17 @@ struct WaveSrc {
     int max_blocks;
 };
 
-template <int D, int KS>
+template <int D, int KS, bool F8>
 __device__ __forceinline__ WaveSrc make_wave_src(const AttnParams &p, int kh)
 {
+    constexpr int ESZ = F8 ? 1 : 2;                    // bytes of a pool element
     WaveSrc ws;
     ws.bt = p.bt;
     ws.new_k = reinterpret_cast<const char *>(p.k_new);
     ws.new_v = reinterpret_cast<const char *>(p.v_new);
-    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * (kPage * D * 2);
-    ws.page_bytes = 2 * p.Hkv * (kPage * D * 2);
-    ws.v_delta = p.Hkv * (kPage * D * 2);
+    ws.pool_k = reinterpret_cast<const char *>(p.pages) + (size_t)kh * (kPage * D * ESZ);
+    ws.page_bytes = 2 * p.Hkv * (kPage * D * ESZ);
+    ws.v_delta = p.Hkv * (kPage * D * ESZ);
     ws.stage_new_bytes = (kBNW * KS) * (p.Hkv * D * 2);
     ws.wave_new_bytes = 16 * (p.Hkv * D * 2);
     ws.max_blocks = p.max_blocks;
@@ -164,10 +165,11 @@ struct StageLoads {
     uint32_t kdst;              // LDS byte address of the K rows; the V rows are 2 * STAGE_BYTES further
     int j0, limit;              // first key row, and the end of the key range it belongs to
     uint32_t ko, vo;            // per-lane byte offsets of the first instruction's rows, K and V
+    bool codes;                 // the rows are FP8 codes of a pool of codes: they travel through registers (fetch_stage_codes)
 };
 
 // Where stage `it` of a job comes from.  Returns whether all 16 rows exist.
-template <int D, int KS>
+template <int D, int KS, bool F8 = false>
 __device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const WaveSrc &ws, const LaneOffsets<D> &lo, int page, int it,
                                                      int wave, int new_row_bytes, uint32_t k_lds, StageLoads &sl)
 {
@@ -178,6 +180,7 @@ __device__ __forceinline__ bool describe_stage_loads(const JobSrc &src, const Wa
     sl.j0 = (ctx ? it : jn) * STAGE + 16 * wave;
     sl.limit = ctx ? src.L : src.n_new;
     sl.kdst = k_lds + wave * (16 * D * 2);
+    sl.codes = F8 && ctx;
     // (a lane's row is further away in k_new / v_new, whose rows are Hkv*D*2 bytes apart, than in a page)
     const uint32_t new_extra = ctx ? 0u : (uint32_t)(fresh_lane() / (D / 8)) * (uint32_t)(new_row_bytes - D * 2);
     sl.ko = lo.k_ctx + new_extra;
@@ -228,6 +231,58 @@ __device__ __forceinline__ void issue_stage_loads(const StageLoads &sl, bool ful
     }
 }
 
+// A pool of FP8 codes: the 16 cached key rows a wavefront loads per stage are 16 * D bytes of K and as many of V,
+// each one contiguous (page, kv head) block.  They travel through registers: 16 codes per lane and load (D / 16
+// lanes cover a row), requested where the 16-bit path issues its direct loads and, once arrived, converted to bf16
+// (exactly) and written to the stage buffer in the layout the direct loads produce (write_stage_codes), before
+// the barrier that opens the stage.  The scales are not applied per element (see tile_job).
+template <int D>
+struct StageCodes {
+    u32x4 k[D / 64], v[D / 64];
+};
+
+template <int D>
+__device__ __forceinline__ void fetch_stage_codes(const StageLoads &sl, bool full, StageCodes<D> &sc)
+{
+    constexpr int NL = D / 64, LPR = D / 16, RPL = 64 / LPR;     // loads per matrix, lanes per row, rows per load
+    const int lane = fresh_lane();
+    const char *kb = sl.kb + lane * 16, *vb = sl.vb + lane * 16;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        // rows past the end of the cached context hold whatever the pool holds: they read as zeros
+        const bool ok = full || sl.j0 + RPL * i + lane / LPR < sl.limit;
+        u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+        if (ok) {
+            a = *reinterpret_cast<const u32x4 *>(kb + 1024 * i);
+            b = *reinterpret_cast<const u32x4 *>(vb + 1024 * i);
+        }
+        sc.k[i] = a;
+        sc.v[i] = b;
+    }
+}
+
+// kdst: the wavefront's 16 K rows in the stage buffer; its V rows are v_lds bytes further.
+template <int D>
+__device__ __forceinline__ void write_stage_codes(const StageCodes<D> &sc, char *kdst, uint32_t v_lds)
+{
+    constexpr int NL = D / 64, LPR = D / 16, RPL = 64 / LPR;
+    const int lane = fresh_lane();
+    const int c16 = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int r = RPL * i + lane / LPR;              // row among the wavefront's 16
+        u32x4 lo, hi;
+        codes_to_bf16(sc.k[i], lo, hi);
+        char *row = kdst + r * (D * 2);
+        *reinterpret_cast<u32x4 *>(row + (((2 * c16) ^ k_swizzle<D>(r)) << 4)) = lo;
+        *reinterpret_cast<u32x4 *>(row + (((2 * c16 + 1) ^ k_swizzle<D>(r)) << 4)) = hi;
+        codes_to_bf16(sc.v[i], lo, hi);
+        row += v_lds;
+        *reinterpret_cast<u32x4 *>(row + (((2 * c16) ^ v_swizzle<D>(r)) << 4)) = lo;
+        *reinterpret_cast<u32x4 *>(row + (((2 * c16 + 1) ^ v_swizzle<D>(r)) << 4)) = hi;
+    }
+}
+
 // Physical page of the 16 cached rows wavefront `wave` loads in stage `it` (unused for stages of
 // new keys).  Read through the constant address space: a scalar load, off the vector-memory queue.
 template <int KS>
@@ -255,7 +310,9 @@ __device__ __forceinline__ int new_stages_before(int m, int bm_shift)
 // First every thread looks up where one of the workgroup's rows goes (table in LDS); then rows
 // are copied 8 at a time with all their loads issued before the first store, so that a
 // workgroup has tens of KB in flight.
-template <int D>
+// F8: the pool holds FP8 codes; a row's 16-byte vectors (8 values) are quantised on the way (8 codes, 8 bytes) under
+// the tensor's scale; the pool's layout is the same with half the element size.
+template <int D, bool F8>
 __device__ __forceinline__ void append_rows(const AttnParams &p, unsigned long long *row_dst, int blk, int nblk, int tid, int nthreads)
 {
     constexpr int CH = D / 8, R = 8;
@@ -271,7 +328,7 @@ __device__ __forceinline__ void append_rows(const AttnParams &p, unsigned long l
             }
             const int pos = p.ctx[lo] + (mine - p.cu[lo]);
             const int page = p.bt[(size_t)lo * p.max_blocks + pos / kPage];
-            // of the row's K vector 0 of head 0, in 16-byte units
+            // of the row's K vector 0 of head 0, in units of a vector (16 bytes; 8 bytes of codes)
             row_dst[tid] = (unsigned long long)page * 2 * p.Hkv * (kPage * CH) + (unsigned long long)(pos % kPage) * CH;
         }
         __syncthreads();
@@ -286,7 +343,11 @@ __device__ __forceinline__ void append_rows(const AttnParams &p, unsigned long l
 #pragma unroll
                 for (int r = 0; r < R; ++r) v[r] = src[(size_t)(base + min(r0 + r, rows_here - 1) * nblk) * per_row];
 #pragma unroll
-                for (int r = 0; r < R; ++r) reinterpret_cast<u32x4 *>(p.pages_w)[row_dst[min(r0 + r, rows_here - 1)] + in_page] = v[r];
+                for (int r = 0; r < R; ++r) {
+                    const size_t at = row_dst[min(r0 + r, rows_here - 1)] + in_page;
+                    if constexpr (F8) reinterpret_cast<uint2 *>(p.pages_w)[at] = bf16_to_codes(v[r], which ? p.v_inv : p.k_inv);
+                    else reinterpret_cast<u32x4 *>(p.pages_w)[at] = v[r];
+                }
             }
         }
         __syncthreads();
@@ -453,6 +514,8 @@ struct Carry {
     bf16x8 qf[D / 16];      // Q fragments of the job about to run (requested before the previous job's epilogue)
     int par;                // stage `it` of the job about to run uses stage buffer (it & 1) ^ par
     int page;               // page of this wavefront's rows of the stage after the job's first one
+    StageCodes<D> codes;    // pool of FP8 codes: this wavefront's rows of the job's first stage, if those are cached keys ...
+    bool have_codes;        // ... and requested, not yet in the stage buffer
 };
 
 // Q fragments (B operand of S^T = K Q^T) of a job: lane holds q[t][16*st + 8*half .. +7].  Lanes
@@ -473,7 +536,7 @@ __device__ __forceinline__ void request_q(const AttnParams &p, const Job &J, int
 // all other pieces there merges them and writes the output rows.  Nobody waits for anybody.
 // `next`: the workgroup has a job after this one, N.  On entry the loads of the job's first
 // stage are in flight and cy holds its Q fragments; on exit the same holds for `next`.
-template <int D, int KS>
+template <int D, int KS, bool F8>
 __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_job, const AttnParams *params, uint4 *smem, float (*Mstat)[2][32],
                                          uint32_t (*peek)[64], int *old_stash, int grp, int kh, const Job &J, bool next, const Job &N, Carry<D> &cy,
                                          Handover &ho)
@@ -492,7 +555,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         asm volatile("" ::: "memory");               // keeps this a branch: the reads are not done speculatively
         p = read_params(params);
     }
-    const WaveSrc ws = make_wave_src<D, KS>(p, kh);
+    const WaveSrc ws = make_wave_src<D, KS, F8>(p, kh);
     // The thread id is made opaque per job: values derived from it are then computed where a job
     // needs them instead of being kept in registers across the whole job loop.
     int tid = threadIdx.x;
@@ -547,7 +610,18 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     float lsum = 0.f;        // this lane's share of the running row sum
     // scores are multiplied by c = scale * log2(e), of either sign; a masked score is the infinity
     // that c turns into -inf
-    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.neg ? -p.c : p.c)));
+    const float c_new = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.neg ? -p.c : p.c)));
+    // A pool of FP8 codes: the stage buffers hold the code values of cached keys and values, the scales are applied
+    // where one multiplication serves many elements.  K: the factor on the scores of cached keys is c * k_scale
+    // (scales are positive: the sign of c is that of the scale).  V: O accumulates weight * code value over the
+    // cached keys and is multiplied by v_scale once, before the first block of new keys adds to it (or when the job
+    // ends, if its stage range has none).  The chunk's own rows are not quantised and take no scale.
+    [[maybe_unused]] const float c_ctx = F8 ? __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, c_new * p.k_scale))) : c_new;
+    [[maybe_unused]] const float v_scale = F8 ? __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.v_scale))) : 1.0f;
+    float c = c_new;         // the factor of the block whose weights are being computed
+    [[maybe_unused]] bool o_scaled = src.n_ctx_tiles == 0;
+    [[maybe_unused]] StageCodes<D> cr = cy.codes;
+    [[maybe_unused]] bool have_codes = F8 && cy.have_codes;
     const int blk = lane >> 4, i16 = lane & 15;
 
     // Fragment loads from LDS.  K: lane holds key (row) l32 of a 32-key block, d = 16*st + 8*half .. +7
@@ -613,27 +687,47 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // requests its first K fragments from LDS right away), and handing out the next stage's loads.
     // `pv_before`: a PV product is pending, i.e. deferred loads will meet their issue point before
     // the next stage is entered.
+    // the loads a StageLoads describes: direct loads into the stage buffer, or codes into registers
+    auto issue = [&](const StageLoads &x, bool full) {
+        if (F8 && x.codes) {
+            fetch_stage_codes<D>(x, full, cr);
+            have_codes = true;
+        } else {
+            issue_stage_loads<D, KS>(x, full);
+        }
+    };
+    // codes that have arrived go to this wavefront's rows of the buffer of stage `it`, which nobody reads before the
+    // barrier that follows
+    auto place_codes = [&](int it) {
+        if constexpr (F8) {
+            if (have_codes) {
+                write_stage_codes<D>(cr, reinterpret_cast<char *>(smem) + buf_of(it) + wave * (16 * D * 2), 2 * STAGE_BYTES);
+                have_codes = false;
+            }
+        }
+    };
     auto issue_pending = [&](int point) {
         if (pend && load_point == point) {
-            issue_stage_loads<D, KS>(sl, true);
+            issue(sl, true);
             pend = false;
         }
     };
     auto sync_stage = [&](int it) -> int {
         if (pend) {                                    // rare: the stage had too few blocks to reach the point
-            issue_stage_loads<D, KS>(sl, true);
+            issue(sl, true);
             pend = false;
         }
         wait_vm<0>();
+        place_codes(it);
         __syncthreads();
         return stage_blocks(it);
     };
     const int32_t *bt_row = ws.bt + src.bt_off;      // the job's block-table row
     auto next_stage_loads = [&](int it, int nb, bool pv_before) {
         if (it + 1 < n_stages) {
-            const bool full = describe_stage_loads<D, KS>(src, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
+            const bool full = describe_stage_loads<D, KS, F8>(src, ws, lo, page, it + 1, wave, new_row_bytes, smem_lds + (buf_of(it) ^ STAGE_BYTES), sl);
             if (full && pv_before && nb != 0 && load_point != 0) pend = true;
-            else issue_stage_loads<D, KS>(sl, full);
+            else issue(sl, full);
         }
         page = load_stage_page<KS>(bt_row, ws.max_blocks, it + 2, wave);
     };
@@ -677,7 +771,9 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // to memory.  Memory operations complete in the order they were issued: the first stage waits for all but
         // those stores; the announcement follows at the job's second stage (a job of one stage: when its loop is done).
         wait_vm<kPartialStores<D>>();
-        __builtin_amdgcn_s_barrier();
+        place_codes(it);
+        if constexpr (F8) lds_barrier();
+        else __builtin_amdgcn_s_barrier();
         nblk = stage_blocks(it);
         ho.fresh = false;
     } else {
@@ -685,6 +781,20 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         announce();
     }
     TETRI_MARK((first_job ? 0 : 12) + 3);
+    [[maybe_unused]] auto scale_o = [&]() {          // (pool of FP8 codes) O leaves the units of code values
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[i][v] *= v_scale;
+        o_scaled = true;
+    };
+    // ... before the first block of a stage of new keys, whose scores also take the plain factor
+    [[maybe_unused]] auto stage_kind = [&](bool is_ctx) {
+        if constexpr (F8) {
+            c = is_ctx ? c_ctx : c_new;
+            if (!is_ctx && !o_scaled) scale_o();
+        }
+    };
     while (nblk == 0 && it + 1 < n_stages) {
         next_stage_loads(it, 0, false);
         nblk = sync_stage(++it);
@@ -830,6 +940,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // after the last block.
         auto block = [&](f32x16 &s_cur, f32x16 &s_next) -> bool {
             const bool is_ctx = it < src.n_ctx_tiles;
+            stage_kind(is_ctx);
             const int key0 = (is_ctx ? it : it - src.n_ctx_tiles) * STAGE + kq * kBNW + kb * 32;
             const bool need_mask = is_ctx ? (key0 + 32 > L) : (key0 + 31 > tw0);
             // V fragments of this block: in registers before the stage may be left
@@ -885,11 +996,13 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         auto steady_step = [&](auto buffer) {
             constexpr int cur = decltype(buffer)::value * (int)STAGE_BYTES, nxt = (int)STAGE_BYTES - cur;
             s16x8 vf[2 * DBLK], vf2[2 * DBLK];
+            stage_kind(it < src.n_ctx_tiles);                    // both blocks this step finishes are of stage `it`
             load_k(kf, cur + BLOCK_BYTES);
             softmax_pv(s_a, s_b, vf, std::integral_constant<int, cur>(), [](int) {}, vf2, std::integral_constant<int, cur + BLOCK_BYTES>());
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the second block's V fragments are out of LDS: the stage may be left
             ++it;
             wait_vm<0>();
+            place_codes(it);
             __syncthreads();
             load_k(kf, nxt);
             const int pg = page;                                 // of stage it + 1, which goes where stage it - 1 was
@@ -904,10 +1017,11 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                         st.kdst = smem_lds + cur + wave * (16 * D * 2);
                         st.ko = lo.k_ctx;
                         st.vo = lo.v_ctx;
-                        issue_stage_loads<D, KS>(st, true);
+                        st.codes = F8;
+                        issue(st, true);
                     } else {
-                        const bool full = describe_stage_loads<D, KS>(src, ws, lo, pg, it + 1, wave, new_row_bytes, smem_lds + cur, st);
-                        issue_stage_loads<D, KS>(st, full);
+                        const bool full = describe_stage_loads<D, KS, F8>(src, ws, lo, pg, it + 1, wave, new_row_bytes, smem_lds + cur, st);
+                        issue(st, full);
                     }
                 }
             };
@@ -919,7 +1033,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             // (a step enters stage it + 1: that one has to be a steady stage)
             if (kb == 0 && nblk == NKB && buf_of(it) == 0 && it + 1 < steady_end && stashed && (ho.unit < 0 || ho.announced)) {
                 if (pend) {
-                    issue_stage_loads<D, KS>(sl, true);
+                    issue(sl, true);
                     pend = false;
                 }
                 while (it + 2 < steady_end) {
@@ -932,12 +1046,17 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             if (!block(s_b, s_a)) break;
         }
     }
+    if constexpr (F8) {
+        if (!o_scaled) scale_o();                      // a stage range of cached keys only: the piece leaves in true units
+    }
     // ---- the next job's first stage, into the buffer the job's last stage does not use: every wavefront has left it.
     // The loads travel during this job's epilogue.
     if (next) {
-        const bool full = describe_stage_loads<D, KS>(nsrc, ws, lo, page_n0, n_it_begin, wave, new_row_bytes,
-                                                      smem_lds + (buf_of(n_stages - 1) ^ STAGE_BYTES), sl);
-        issue_stage_loads<D, KS>(sl, full);
+        const bool full = describe_stage_loads<D, KS, F8>(nsrc, ws, lo, page_n0, n_it_begin, wave, new_row_bytes,
+                                                          smem_lds + (buf_of(n_stages - 1) ^ STAGE_BYTES), sl);
+        cy.have_codes = F8 && sl.codes;
+        if (F8 && sl.codes) fetch_stage_codes<D>(sl, full, cy.codes);     // placed by the next job, before its first barrier
+        else issue_stage_loads<D, KS>(sl, full);
     }
     if (ho.unit >= 0 && (!ho.announced || !stashed)) {        // a partial result not announced, or announced at the job's last stage
         wait_vm<0>();
@@ -1126,7 +1245,7 @@ __device__ __forceinline__ void zero_padding_rows(const AttnParams &p, int grp, 
     }
 }
 
-template <int D, int KS>
+template <int D, int KS, bool F8>
 __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnParams p)
 {
     constexpr int STAGE = kBNW * KS;
@@ -1145,7 +1264,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     int abid = blockIdx.x;                           // index in the attention grid
     if (abid >= p.attn_first) {
         if (abid < p.attn_first + p.append_blocks) {
-            append_rows<D>(p, reinterpret_cast<unsigned long long *>(smem), abid - p.attn_first, p.append_blocks, threadIdx.x, NT);
+            append_rows<D, F8>(p, reinterpret_cast<unsigned long long *>(smem), abid - p.attn_first, p.append_blocks, threadIdx.x, NT);
             return;
         }
         abid -= p.append_blocks;
@@ -1173,7 +1292,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     const int kh = magic_div(grp, p.kv_magic);
     const int first_page = min(wave, p.max_blocks - 1), first_page_hi = min(wave + kSlots, p.max_blocks - 1);
 
-    const WaveSrc ws = make_wave_src<D, KS>(p, kh);    // for the first job's first loads; every job derives its own
+    const WaveSrc ws = make_wave_src<D, KS, F8>(p, kh);    // for the first job's first loads; every job derives its own
 
     // ---- the workgroup's first job.  Lane l looks at segment s0 + l (64 at a time); it also fetches
     // what the owner of the job will need next (context length, the pages of the segment's first
@@ -1416,7 +1535,15 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
             return ((const const_i32 *)(uintptr_t)(p.bt + J.src.bt_off))[e];
         };
         constexpr int PPS = kBNW * KS / kPage;           // pages per stage
-        if (kq == 0) {
+        cy.have_codes = false;
+        if (F8 && J.it_begin < J.src.n_ctx_tiles) {
+            // a pool of FP8 codes and a first stage of cached keys: every wavefront requests the codes of its own rows
+            if (J.it_begin != 0 || !pages_fetched) page = row_entry(J.it_begin * PPS + wave);
+            StageLoads sl;
+            const bool full = describe_stage_loads<D, KS, F8>(J.src, ws, lo, page, J.it_begin, wave, new_row_bytes, lds_address(smem), sl);
+            fetch_stage_codes<D>(sl, full, cy.codes);
+            cy.have_codes = true;
+        } else if (kq == 0) {
             if (J.it_begin != 0 || !pages_fetched) {     // the lookup fetched the pages of stage 0 of its first tile
                 page = row_entry(J.it_begin * PPS + wave);
                 page_hi = row_entry(J.it_begin * PPS + wave + kSlots);
@@ -1453,7 +1580,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
                 --n_later;
             }
         }
-        tile_job<D, KS>(p, first, &params, smem, Mstat, peek, old_stash, grp, kh, J, more, N, cy, ho);
+        tile_job<D, KS, F8>(p, first, &params, smem, Mstat, peek, old_stash, grp, kh, J, more, N, cy, ho);
         if (!more) break;
         J = N;
     }
@@ -1476,18 +1603,23 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
     TETRI_MARK(7);
 }
 
-template <int D, int KS>
+template <int D, int KS, bool F8>
 hipError_t launch(const AttnParams &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL((attn_tile_kernel<D, KS>), dim3(p.attn_grid + p.append_blocks), dim3(kSlots * KS * 64), 0, stream, p);
+    hipLaunchKernelGGL((attn_tile_kernel<D, KS, F8>), dim3(p.attn_grid + p.append_blocks), dim3(kSlots * KS * 64), 0, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream)
+hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, bool fp8_pool, hipStream_t stream)
 {
+    if (fp8_pool) {
+        if (h->cfg.head_dim == 128)
+            return key_parts == 2 ? launch<128, 2, true>(p, stream) : launch<128, 1, true>(p, stream);
+        return key_parts == 2 ? launch<64, 2, true>(p, stream) : launch<64, 1, true>(p, stream);
+    }
     if (h->cfg.head_dim == 128)
-        return key_parts == 2 ? launch<128, 2>(p, stream) : launch<128, 1>(p, stream);
-    return key_parts == 2 ? launch<64, 2>(p, stream) : launch<64, 1>(p, stream);
+        return key_parts == 2 ? launch<128, 2, false>(p, stream) : launch<128, 1, false>(p, stream);
+    return key_parts == 2 ? launch<64, 2, false>(p, stream) : launch<64, 1, false>(p, stream);
 }

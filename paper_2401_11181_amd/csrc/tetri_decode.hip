@@ -125,13 +125,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
         for (int i = 0; i < NL; ++i) {
             const int r = i * RPI + lane / LPR, c16 = lane % LPR;
             u32x4 lo, hi;
-#pragma unroll
-            for (int w = 0; w < 2; ++w) {
-                lo[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][w], 1.0f, false));
-                lo[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][w], 1.0f, true));
-                hi[2 * w] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][2 + w], 1.0f, false));
-                hi[2 * w + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[i][2 + w], 1.0f, true));
-            }
+            codes_to_bf16(raw[i], lo, hi);
             const int swz = is_v ? v_swizzle<D>(r) : k_swizzle<D>(r);
             char *row = my + (is_v ? TILE_BYTES : 0) + r * ROW;
             *reinterpret_cast<u32x4 *>(row + (((2 * c16) ^ swz) << 4)) = lo;
@@ -161,22 +155,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_attn_kernel(DecodeParam
                           + ((size_t)(L % kPage) * ROW + chunk * 16) / 2 * ESZ;
         const u32x4 v = *reinterpret_cast<const u32x4 *>((which ? new_v : new_k) + chunk * 16);
         if constexpr (FP8) {
-            const float inv = which ? p.v_inv : p.k_inv;
-            uint32_t codes[2];
-#pragma unroll
-            for (int w = 0; w < 2; ++w) {
-                float y[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t word = v[2 * w + e / 2];
-                    const float x = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
-                    y[e] = __builtin_fminf(__builtin_fmaxf(x * inv, -448.0f), 448.0f);
-                }
-                int c = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
-                c = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], c, true);
-                codes[w] = (uint32_t)c;
-            }
-            *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(p.pages_w) + at) = make_uint2(codes[0], codes[1]);
+            *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(p.pages_w) + at) = bf16_to_codes(v, which ? p.v_inv : p.k_inv);
         } else {
             *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(p.pages_w) + at) = v;
         }

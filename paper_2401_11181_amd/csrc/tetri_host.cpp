@@ -375,7 +375,8 @@ tetri_status tetri_decode_attn_append(tetri_ctx *h, const void *q, const void *k
 
 static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
                                 const void *kv_pages, void *kv_pages_w, const int32_t *block_table, const int32_t *cu,
-                                const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream)
+                                const int32_t *ctx_lens, int32_t num_segs, float scale, void *out, void *stream,
+                                bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f)
 {
     const void *ptrs[] = {q, k_new, v_new, kv_pages, out};
     const char *names[] = {"q", "k_new", "v_new", "kv_pages", "out"};
@@ -383,7 +384,11 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     if (st != TETRI_OK) return st;
     if (!block_table || !cu || !ctx_lens) return fail(h, TETRI_ERR_INVALID_ARG, "%s: null metadata pointer", fn);
     if (!std::isfinite(scale)) return fail(h, TETRI_ERR_INVALID_ARG, "%s: scale is not finite", fn);
+    if (fp8 && !(std::isfinite(k_scale) && std::isfinite(v_scale) && k_scale > 0.f && v_scale > 0.f))
+        return fail(h, TETRI_ERR_INVALID_ARG, "%s: k_scale and v_scale must be positive and finite", fn);
     AttnParams p;
+    p.k_scale = k_scale; p.v_scale = v_scale;
+    p.k_inv = 1.0f / k_scale; p.v_inv = 1.0f / v_scale;
     p.q = static_cast<const uint16_t *>(q);
     p.k_new = static_cast<const uint16_t *>(k_new);
     p.v_new = static_cast<const uint16_t *>(v_new);
@@ -490,7 +495,7 @@ static tetri_status attn_common(const char *fn, tetri_ctx *h, const void *q, con
     p.kv_magic = magic((uint32_t)(p.g / p.hpw));
     if ((uint64_t)p.attn_grid * (uint64_t)(p.tiles + G + 1) >= 0x100000000ull)
         return fail(h, TETRI_ERR_UNSUPPORTED, "%s: chunk_size x heads too large for one launch", fn);
-    hipError_t e = tetri_launch_attn(h, p, key_parts, hs);
+    hipError_t e = tetri_launch_attn(h, p, key_parts, fp8, hs);
     if (e != hipSuccess) return fail(h, TETRI_ERR_HIP, "%s: launch failed: %s", fn, hipGetErrorString(e));
     if (shares) {
         h->counter_set = 1 - h->counter_set;
@@ -517,6 +522,16 @@ tetri_status tetri_chunk_prefill_attn_append(tetri_ctx *h, const void *q, const 
 {
     return attn_common("tetri_chunk_prefill_attn_append", h, q, k_new, v_new, kv_pages, kv_pages, block_table, cu,
                        ctx_lens, num_segs, scale, out, stream);
+}
+
+tetri_status tetri_chunk_prefill_attn_fp8(tetri_ctx *h, const void *q, const void *k_new, const void *v_new,
+                                          void *kv_pages_fp8, const int32_t *block_table, const int32_t *cu,
+                                          const int32_t *ctx_lens, int32_t num_segs, float scale, float k_scale,
+                                          float v_scale, int32_t append, void *out, void *stream)
+{
+    if (append != 0 && append != 1) return fail(h, TETRI_ERR_INVALID_ARG, "tetri_chunk_prefill_attn_fp8: append must be 0 or 1");
+    return attn_common("tetri_chunk_prefill_attn_fp8", h, q, k_new, v_new, kv_pages_fp8, append ? kv_pages_fp8 : nullptr,
+                       block_table, cu, ctx_lens, num_segs, scale, out, stream, true, k_scale, v_scale);
 }
 
 tetri_status tetri_validate_chunk(tetri_ctx *h, const int32_t *block_table, const int32_t *cu, const int32_t *ctx_lens,

@@ -63,6 +63,9 @@ struct AttnParams {
     int32_t attn_first;   // attention workgroups that precede them in the grid (a multiple of 8)
     float c;              // |scale| * log2(e)
     int32_t neg;          // 1 if scale < 0
+    // FP8 cache (the kernel variant that reads a pool of E4M3 codes): cached K / V = value(code) * scale
+    float k_scale, v_scale;
+    float k_inv, v_inv;   // fl32(1 / scale): the fused append quantises with them
 };
 
 struct AppendParams {
@@ -98,7 +101,7 @@ struct DecodeParams {
     float out_scale;      // factor on the finished output: v_scale for an FP8 pool, else 1
 };
 
-hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, hipStream_t stream);
+hipError_t tetri_launch_attn(const tetri_ctx *h, const AttnParams &p, int key_parts, bool fp8_pool, hipStream_t stream);
 hipError_t tetri_launch_kv_transfer(const tetri_ctx *h, const TransferParams &p, int32_t row_units, int32_t tiles,
                                     bool to_pool, hipStream_t stream);
 hipError_t tetri_launch_kv_export_fp8(const tetri_ctx *h, const TransferParams &p, int32_t tiles, hipStream_t stream);

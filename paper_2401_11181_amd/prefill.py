@@ -83,6 +83,11 @@ class ChunkedPrefill:
         cu, ctx, bt, S = self.meta[c]
         self.handle.tetri_chunk_prefill_attn_append(q, k_new, v_new, kv_pages, bt, cu, ctx, S, scale, out, stream)
 
+    def attn_fp8(self, c, q, k_new, v_new, kv_pages_fp8, scale, k_scale, v_scale, append, out, stream=None):
+        cu, ctx, bt, S = self.meta[c]
+        self.handle.tetri_chunk_prefill_attn_fp8(q, k_new, v_new, kv_pages_fp8, bt, cu, ctx, S, scale, k_scale, v_scale,
+                                                 append, out, stream)
+
     def validate(self, c):
         cu, ctx, bt, S = self.meta[c]
         self.handle.tetri_validate_chunk(bt, cu, ctx, S)

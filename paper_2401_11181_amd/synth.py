@@ -123,3 +123,14 @@ def pool_sentinel(shape, dtype=torch.bfloat16, device="cpu"):
     t = torch.empty(shape, dtype=torch.int16, device=device)
     t.fill_(0x3B5A)                       # bf16 0x3B5A ~ 3.3e-3, finite
     return t.view(dtype) if dtype != torch.int16 else t
+
+
+def random_kv_codes(shape, seed, k_scale, v_scale, std=1.0):
+    """A pool [num_pages,2,Hkv,P,D] of FP8 E4M3 codes (uint8) whose values times the tensor's scale are about
+    N(0, std^2): normal draws divided by the scale, turned into codes by torch's float8_e4m3fn conversion (an
+    input generator: both sides read the codes, neither the draws)."""
+    g = torch.Generator().manual_seed(int(seed))
+    x = torch.randn(shape, generator=g, dtype=torch.float32) * std
+    x[:, 0] /= k_scale
+    x[:, 1] /= v_scale
+    return x.clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)

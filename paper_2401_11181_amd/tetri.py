@@ -85,6 +85,8 @@ def lib():
         L.tetri_kv_import_fp8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
         L.tetri_decode_attn_fp8.restype = i32
         L.tetri_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, i32, vp, vp]
+        L.tetri_chunk_prefill_attn_fp8.restype = i32
+        L.tetri_chunk_prefill_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, f32, f32, i32, vp, vp]
         L.tetri_kv_export.restype = i32
         L.tetri_kv_export.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int64, vp, vp]
         L.tetri_kv_import.restype = i32
@@ -280,6 +282,13 @@ class Tetri:
                                                 _ptr(block_table), _ptr(ctx_lens), int(num_reqs), int(max_ctx_len),
                                                 float(scale), float(k_scale), float(v_scale), int(append), _ptr(out),
                                                 _stream(stream)))
+
+    def tetri_chunk_prefill_attn_fp8(self, q, k_new, v_new, kv_pages_fp8, block_table, cu_chunk_q_lens, ctx_lens, num_segs,
+                                     scale, k_scale, v_scale, append, out, stream=None):
+        self._check(lib().tetri_chunk_prefill_attn_fp8(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages_fp8),
+                                                       _ptr(block_table), _ptr(cu_chunk_q_lens), _ptr(ctx_lens),
+                                                       int(num_segs), float(scale), float(k_scale), float(v_scale),
+                                                       int(append), _ptr(out), _stream(stream)))
 
     def tetri_kv_export(self, kv_pages, block_table, cu_tokens, first_tokens, num_reqs, total_tokens, buf,
                         stream=None):

@@ -18,16 +18,8 @@ def workload_tensors(w):
     return qs, ks, vs, synth.place_pages(w)
 
 
-def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False, variant=0, fused=False):
-    """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
-    sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
-                          w.num_pages, tables, device=DEV, page_size=w.page_size)
-    # variants 0 / 1 / 2: the library's choice / 4-wavefront / 8-wavefront workgroups, each with the library's
-    # choice of how the work is handed out; 10 / 11: 8- / 4-wavefront workgroups, tail mode with every key range of
-    # two or more stages handing its last third to a helper workgroup (the library itself only does so for long
-    # ones); 13: half of it (helpers settle their first tile late); 12: one workgroup per row tile, nothing
-    # divided; 14 / 15: stream mode with 5 workgroups per head group, 8 / 4 wavefronts; 16: with 2 (every workgroup
-    # runs many jobs); 17: with 200 (a stage per workgroup: as many pieces per tile as it has stages)
+def set_variant(sess, variant):
+    """Kernel variant of a session (see gpu_prefill)."""
     sess.handle.tetri_set_option("attn_variant", variant if variant < 10 else (1 if variant in (11, 15) else 2))
     if variant in (10, 11, 13):
         sess.handle.tetri_set_option("split_min_stages", 2)
@@ -38,6 +30,19 @@ def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_c
         sess.handle.tetri_set_option("split_keys", 0)
     if variant in (14, 15, 16, 17):
         sess.handle.tetri_set_option("stream_wgs", {14: 5, 15: 5, 16: 2, 17: 200}[variant])
+
+
+def gpu_prefill(w, qs, ks, vs, tables, append_first=False, pad_fill=None, keep_chunks=False, variant=0, fused=False):
+    """Run the whole batch on the GPU.  Returns (outs per request [n,Hq,D] bf16 cpu, pool tensor, session)."""
+    sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                          w.num_pages, tables, device=DEV, page_size=w.page_size)
+    # variants 0 / 1 / 2: the library's choice / 4-wavefront / 8-wavefront workgroups, each with the library's
+    # choice of how the work is handed out; 10 / 11: 8- / 4-wavefront workgroups, tail mode with every key range of
+    # two or more stages handing its last third to a helper workgroup (the library itself only does so for long
+    # ones); 13: half of it (helpers settle their first tile late); 12: one workgroup per row tile, nothing
+    # divided; 14 / 15: stream mode with 5 workgroups per head group, 8 / 4 wavefronts; 16: with 2 (every workgroup
+    # runs many jobs); 17: with 200 (a stage per workgroup: as many pieces per tile as it has stages)
+    set_variant(sess, variant)
     pool = synth.pool_sentinel((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), device=DEV)
     dq = [t.to(DEV) for t in qs]
     dk = [t.to(DEV) for t in ks]
@@ -133,3 +138,56 @@ def oracle_chunk_samples(oracle, w, segs, q_chunk, k_chunk, v_chunk, ks, vs, row
             oracle.kv_append(kc, vc, pool, bt[i:i + 1], [0, start], [0])
     cu, ctx = opacker.chunk_arrays(segs)
     return oracle.chunk_prefill_attn_samples(q_chunk, k_chunk, v_chunk, pool, bt, cu, ctx, w.scale, rows, heads)
+
+
+NAN_CODE = 0x7F     # the FP8 pattern that is not a number: fills unused slots of pools of codes, so that a stray read shows
+
+
+def gpu_prefill_fp8(w, qs, ks, vs, tables, k_scale, v_scale, variant=0, pad_fill=None):
+    """The whole batch on the GPU over a cache of FP8 codes: every chunk attends to the codes cached so far and
+    its own rows, and caches the codes of its rows (one fused launch per chunk).  Returns (outs per request, pool of
+    codes [uint8 tensor], session)."""
+    sess = ChunkedPrefill(w.prompt_lens, w.order, w.chunk_size, w.num_q_heads, w.num_kv_heads, w.head_dim,
+                          w.num_pages, tables, device=DEV, page_size=w.page_size)
+    set_variant(sess, variant)
+    pool = torch.full((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), NAN_CODE, dtype=torch.uint8, device=DEV)
+    dq, dk, dv = [t.to(DEV) for t in qs], [t.to(DEV) for t in ks], [t.to(DEV) for t in vs]
+    outs = [torch.zeros_like(t) for t in qs]
+    for c in range(sess.n_chunks):
+        q, k, v = sess.gather_chunk(dq, c), sess.gather_chunk(dk, c), sess.gather_chunk(dv, c)
+        segs = sess.chunk_segments(c)
+        n_real = sum(n for _, _, n in segs)
+        if pad_fill is not None and n_real < w.chunk_size:
+            q[n_real:], k[n_real:], v[n_real:] = pad_fill, pad_fill, pad_fill
+        out = torch.full((w.chunk_size, w.num_q_heads, w.head_dim), 7.0, dtype=torch.bfloat16, device=DEV)
+        sess.attn_fp8(c, q, k, v, pool, w.scale, k_scale, v_scale, 1, out)
+        torch.cuda.synchronize()
+        o = out.cpu()
+        at = 0
+        for req, start, n in segs:
+            outs[req][start:start + n] = o[at:at + n]
+            at += n
+        assert (o[n_real:].view(torch.int16) == 0).all(), "padding rows of out must be +0"
+    return outs, pool, sess
+
+
+def oracle_prefill_fp8(w, qs, ks, vs, tables, k_scale, v_scale):
+    """The same batch through the CPU oracle of prefill over a cache of codes.  Returns (outs, pool of codes)."""
+    from oracle import prefill_fp8, tetri_oracle
+    codes = np.full((w.num_pages, 2, w.num_kv_heads, w.page_size, w.head_dim), NAN_CODE, dtype=np.uint8)
+    qf, kf, vf = [t.float().numpy() for t in qs], [t.float().numpy() for t in ks], [t.float().numpy() for t in vs]
+    outs = [np.zeros(t.shape, dtype=np.float64) for t in qf]
+    max_blocks = max(len(t) for t in tables)
+    for segs in opacker.pack_chunks(w.prompt_lens, w.order, w.chunk_size):
+        cu, ctx = opacker.chunk_arrays(segs)
+        bt = np.zeros((len(segs), max_blocks), dtype=np.int32)
+        for i, (req, _s, _n) in enumerate(segs):
+            bt[i, :len(tables[req])] = tables[req]
+        q = tetri_oracle.gather_chunk(qf, segs, w.chunk_size)
+        k = tetri_oracle.gather_chunk(kf, segs, w.chunk_size)
+        v = tetri_oracle.gather_chunk(vf, segs, w.chunk_size)
+        o = prefill_fp8.chunk_prefill_attn_fp8(q, k, v, codes, bt, cu, ctx, w.scale, k_scale, v_scale)
+        prefill_fp8.prefill_append_fp8(k, v, codes, bt, cu, ctx, k_scale, v_scale)
+        for i, (req, start, n) in enumerate(segs):
+            outs[req][start:start + n] = o[cu[i]:cu[i] + n]
+    return outs, codes

@@ -466,6 +466,25 @@ def main():
         }
         del xbuf
 
+    # ---- the same chunks over a cache of FP8 E4M3 codes (this build's extension): every chunk's fused launch
+    # (attention over the codes cached so far + quantising append), repeated on one set of buffers like warm_cache
+    if int(np.prod(pool.shape)) <= (16 << 30):
+        k8 = v8 = float(w.std) / 32.0
+        pool8 = torch.zeros(tuple(pool.shape), dtype=torch.uint8, device=dev)
+        for c in range(nC):
+            pipe.launch_fused_fp8(c, pool8, k8, v8, 1)
+        torch.cuda.synchronize()
+        n8 = min(nC, 8)
+        fp8_ms = [group_time(lambda i, c=c: pipe.launch_fused_fp8(c, pool8, k8, v8, 1)) for c in range(n8)]
+        ref_ms = warm_attn_ms if warm_attn_ms is not None else [float(x) for x in attn_ms[:n8]]
+        result["fp8_prefill"] = {
+            "kernel": "attn_tile_kernel<D, KS, FP8> (tetri_chunk_prefill_attn_fp8 with append, the first %d chunks)" % n8,
+            "attn_ms_median": [round(x, 5) for x in fp8_ms],
+            "tflops": round(float(sum(flops[:n8])) / (sum(fp8_ms) * 1e-3) / 1e12, 1),
+            "time_vs_16_bit_pool": round(sum(fp8_ms) / sum(ref_ms[:n8]), 3) if fused else None,
+        }
+        del pool8
+
     # ---- the decode instance's counterpart (Sec. 3.4): one decode iteration of 64 requests with 2048
     # cached tokens each, same head shape, scattered pages; bytes = the cached K and V, read once
     dB, dctx = 64, 2048

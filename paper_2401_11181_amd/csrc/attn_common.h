@@ -13,6 +13,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+// Accesses through these go out as global-memory instructions whatever the compiler knows about the pointer.  (An
+// access through a generic pointer is a FLAT instruction, which also counts as an LDS operation: every later wait
+// for LDS reads then waits for it.)
+typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+typedef __attribute__((address_space(1))) u32x4 global_u32x4_w;
 
 constexpr int kPage = 16;     // tokens per KV page
 constexpr int kXcd = 8;       // XCDs (L2 domains) workgroups are dealt to round-robin
@@ -231,6 +236,13 @@ __device__ __forceinline__ uint2 bf16_to_codes(const u32x4 &v, float inv)
         codes[w] = (uint32_t)c;
     }
     return make_uint2(codes[0], codes[1]);
+}
+
+// Relaxed device-scope fetch-and-add on a word of global memory, as a global-memory instruction (see above).
+__device__ __forceinline__ int atomic_add_global(int32_t *p, int v)
+{
+    return __hip_atomic_fetch_add(reinterpret_cast<__attribute__((address_space(1))) int32_t *>((uintptr_t)p), v, __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Everything a wavefront needs to know about where its workgroup's keys come from.

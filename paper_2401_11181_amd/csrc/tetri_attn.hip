@@ -253,8 +253,10 @@ __device__ __forceinline__ void fetch_stage_codes(const StageLoads &sl, bool ful
         const bool ok = full || sl.j0 + RPL * i + lane / LPR < sl.limit;
         u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
         if (ok) {
-            a = *reinterpret_cast<const u32x4 *>(kb + 1024 * i);
-            b = *reinterpret_cast<const u32x4 *>(vb + 1024 * i);
+            // (through the global address space: a load through a generic pointer also counts as an LDS operation,
+            // and the next wait for LDS reads would wait for it)
+            a = *reinterpret_cast<global_u32x4 *>((uintptr_t)(kb + 1024 * i));
+            b = *reinterpret_cast<global_u32x4 *>((uintptr_t)(vb + 1024 * i));
         }
         sc.k[i] = a;
         sc.v[i] = b;
@@ -413,7 +415,9 @@ __device__ __forceinline__ void store_out_rows(uint16_t *orow, int half, F &&chu
         for (int q4 = 0; q4 < 4; q4 += 2) {
             uint2 a = chunk(db, q4), b = chunk(db, q4 + 1);
             asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %2\n\tv_permlane32_swap_b32 %1, %3\n\ts_nop 1" : "+v"(a.x), "+v"(a.y), "+v"(b.x), "+v"(b.y));
-            *reinterpret_cast<uint4 *>(orow + db * 32 + (q4 + half) * 8) = make_uint4(a.x, a.y, b.x, b.y);
+            // (a store through the global address space: where the pointer comes from the parameters' copy in LDS the
+            // compiler knows no address space for it, and a generic access also counts as an LDS operation)
+            *reinterpret_cast<global_u32x4_w *>((uintptr_t)(orow + db * 32 + (q4 + half) * 8)) = u32x4{a.x, a.y, b.x, b.y};
         }
 }
 
@@ -524,9 +528,9 @@ template <int D>
 __device__ __forceinline__ void request_q(const AttnParams &p, const Job &J, int head, int rbk, int lane, bf16x8 (&qf)[D / 16])
 {
     const int t = J.t0 + 32 * rbk + (lane & 31);
-    const uint4 *qp = reinterpret_cast<const uint4 *>(p.q + ((size_t)(J.seg_cu + (t < J.n_s ? t : 0)) * p.Hq + head) * D);
+    const global_u32x4 *qp = reinterpret_cast<const global_u32x4 *>((uintptr_t)(p.q + ((size_t)(J.seg_cu + (t < J.n_s ? t : 0)) * p.Hq + head) * D));
 #pragma unroll
-    for (int st = 0; st < D / 16; ++st) qf[st] = __builtin_bit_cast(bf16x8, qp[2 * st + (lane >> 5)]);
+    for (int st = 0; st < D / 16; ++st) qf[st] = __builtin_bit_cast(bf16x8, u32x4(qp[2 * st + (lane >> 5)]));
 }
 
 // One job: stages [J.it_begin, J.it_end) of one row tile of one head group.  When the stage range is
@@ -616,9 +620,12 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
     // (scales are positive: the sign of c is that of the scale).  V: O accumulates weight * code value over the
     // cached keys and is multiplied by v_scale once, before the first block of new keys adds to it (or when the job
     // ends, if its stage range has none).  The chunk's own rows are not quantised and take no scale.
-    [[maybe_unused]] const float c_ctx = F8 ? __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, c_new * p.k_scale))) : c_new;
-    [[maybe_unused]] const float v_scale = F8 ? __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.v_scale))) : 1.0f;
-    float c = c_new;         // the factor of the block whose weights are being computed
+    // (c: the factor of the block whose weights are being computed; what the change to new keys needs is read from the
+    // launch parameters when it happens, once per job, not kept in registers across the stages of cached keys)
+    float c = c_new;
+    if constexpr (F8) {
+        if (J.it_begin < src.n_ctx_tiles) c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, c_new * p.k_scale)));
+    }
     [[maybe_unused]] bool o_scaled = src.n_ctx_tiles == 0;
     [[maybe_unused]] StageCodes<D> cr = cy.codes;
     [[maybe_unused]] bool have_codes = F8 && cy.have_codes;
@@ -760,7 +767,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             stashed = true;
         }
         if (ho.unit >= 0 && !ho.announced) {
-            if (fresh_lane() == 0) old = atomicAdd(p.counters + ho.unit, 1);
+            if (fresh_lane() == 0) old = atomic_add_global(p.counters + ho.unit, 1);
             ho.announced = true;
             stashed = false;
         }
@@ -781,17 +788,22 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         announce();
     }
     TETRI_MARK((first_job ? 0 : 12) + 3);
-    [[maybe_unused]] auto scale_o = [&]() {          // (pool of FP8 codes) O leaves the units of code values
+    // (pool of FP8 codes) O leaves the units of code values; scores take the plain factor from here on.  Called behind
+    // the job's first barrier: the copy of the launch parameters in LDS is complete.
+    [[maybe_unused]] auto scale_o = [&]() {
+        asm volatile("" ::: "memory");
+        const AttnParams pq = read_params(params);
+        const float v_scale = pq.v_scale;
 #pragma unroll
         for (int i = 0; i < DBLK; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[i][v] *= v_scale;
+        c = pq.neg ? -pq.c : pq.c;
         o_scaled = true;
     };
-    // ... before the first block of a stage of new keys, whose scores also take the plain factor
+    // ... before the first block of new keys
     [[maybe_unused]] auto stage_kind = [&](bool is_ctx) {
         if constexpr (F8) {
-            c = is_ctx ? c_ctx : c_new;
             if (!is_ctx && !o_scaled) scale_o();
         }
     };
@@ -1175,7 +1187,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
             }
             coherent_stores_done();                  // this wavefront's partial is in memory ...
             int arrived = 0;
-            if (lane_e == 0) arrived = atomicAdd(pe.counters + unit, 1);     // ... before it is announced
+            if (lane_e == 0) arrived = atomic_add_global(pe.counters + unit, 1);     // ... before it is announced
             arrived = __builtin_amdgcn_readfirstlane(arrived);
             if (arrived != J.npieces - 1) {          // not the last one: whoever is finishes the tile
                 TETRI_MARK((first_job ? 0 : 12) + 6);

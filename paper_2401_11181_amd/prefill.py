@@ -212,6 +212,16 @@ class PrefillPipeline:
         if rc != tetri.TETRI_OK:
             raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
 
+    def launch_fused_fp8(self, c, kv_pages_fp8, k_scale, v_scale, append=1, stream=None):
+        """Chunk c over a pool of FP8 codes: attention and, with append, the quantising append, in one launch."""
+        import ctypes
+        h, q, k, v, _pool, bt, cu, ctx, S, scale, o = self._attn_args[c]
+        rc = self._lib.tetri_chunk_prefill_attn_fp8(h, q, k, v, ctypes.c_void_p(kv_pages_fp8.data_ptr()), bt, cu, ctx, S, scale,
+                                                    ctypes.c_float(k_scale), ctypes.c_float(v_scale), ctypes.c_int32(append), o,
+                                                    stream or tetri._stream(None))
+        if rc != tetri.TETRI_OK:
+            raise tetri.TetriError(rc, tetri.tetri_last_error(self.handle))
+
     def launch_append(self, c, stream=None):
         rc = self._lib.tetri_kv_append(*self._app_args[c], stream or tetri._stream(None))
         if rc != tetri.TETRI_OK:

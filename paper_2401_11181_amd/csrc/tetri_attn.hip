@@ -1003,7 +1003,11 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
         // it + 1 are issued; on exit the same holds for stage it + 1 in buffer 1 - B.
         const int ctx_whole = L / STAGE;                       // stages before it are whole stages of cached keys
         // (new key j is visible to local row t >= j: stage x of new keys is unmasked for rows from tw0 on if (x + 1) * STAGE <= tw0 + 1)
-        const int steady_end = min(n_stages, L % STAGE == 0 ? ctx_whole + (tw0 + 1) / STAGE : ctx_whole);
+        const int steady_whole = min(n_stages, L % STAGE == 0 ? ctx_whole + (tw0 + 1) / STAGE : ctx_whole);
+        // A step finishes stage `it` and enters stage it + 1, of which it only computes the raw scores of the first
+        // block: the stage behind the last whole one may be entered that way too if the wavefront has a block there (a
+        // ragged or masked stage: its loads are described the general way, its blocks are the general ones).
+        const int steady_end = steady_whole + (int)(steady_whole < n_stages && stage_blocks(steady_whole) != 0);
         f32x16 s_a = qk(kf), s_b;
         auto steady_step = [&](auto buffer) {
             constexpr int cur = decltype(buffer)::value * (int)STAGE_BYTES, nxt = (int)STAGE_BYTES - cur;
@@ -1053,6 +1057,7 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                     steady_step(std::integral_constant<int, 1>());
                 }
                 if (it + 1 < steady_end) steady_step(std::integral_constant<int, 0>());
+                nblk = stage_blocks(it);                 // (fewer than all only in the stage behind the last whole one)
             }
             if (!block(s_a, s_b)) break;
             if (!block(s_b, s_a)) break;

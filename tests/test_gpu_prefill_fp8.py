@@ -200,6 +200,18 @@ def test_gqa_shape_sampled():
     sampled(w, long_mid, 413, 16)
 
 
+def test_packed_shape_sampled():
+    """286 short prompts in 64 chunks of 512 at 40 x 128 heads: the chunk with the most segments, and one whose first
+    segment continues a prompt that began in the chunk before (cached tokens of one segment, none of the others)."""
+    w = synth.sharp(synth.workload("packed"))
+    plan = opacker.pack_chunks(w.prompt_lens, w.order, w.chunk_size)
+    most = max(range(len(plan)), key=lambda i: len(plan[i]))
+    cont = max(range(len(plan)), key=lambda i: plan[i][0][1])          # the longest carried-over context
+    assert plan[cont][0][1] > 0
+    sampled(w, most, 415, 24)
+    sampled(w, cont, 416, 24)
+
+
 @pytest.mark.parametrize("chunk", [1024, 4096])
 def test_large_chunk_sizes_sampled(chunk):
     """ChunkSize 1024 / 4096 at 40 x 128 heads over an 8192-token prompt: the second chunk."""

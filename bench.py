@@ -19,8 +19,9 @@ buffer sets.
 Beside the contract's fields the line carries stand-alone measurements taken after the timed region:
 `per_chunk`, `roofline.per_chunk_bound_frac` (each chunk against the roofline that binds it:
 max(flops / MFMA peak, bytes / HBM peak) / duration), `append`, `kv_transfer` (request-level KV export /
-import, Sec. 3.3.4), `decode` (one decode iteration of 64 requests x 2048 cached tokens on the same head
-shape) and `cpu_baseline` (the CPU oracle on this machine's host cores over a bounded sample of the same
+import, Sec. 3.3.4), `fp8_prefill` (the first chunks' fused launches over a cache of FP8 codes, against the same
+launches over the 16-bit pool), `decode` (one decode iteration of 64 requests x 2048 cached tokens on the same head
+shape, 16-bit and FP8 cache) and `cpu_baseline` (the CPU oracle on this machine's host cores over a bounded sample of the same
 workload).  Other modes: --policy / --sched-batch (prefill scheduler, Sec. 3.3.2), --chunk-size /
 --prompt-len, --sweep (the ChunkSize saturation experiment of Sec. 2.2 in one run), --layer-sweep (the same
 for a whole decoder layer), --export (KV export inside the step).

@@ -18,7 +18,8 @@ buffer sets.
 
 Beside the contract's fields the line carries stand-alone measurements taken after the timed region:
 `per_chunk`, `roofline.per_chunk_bound_frac` (each chunk against the roofline that binds it:
-max(flops / MFMA peak, bytes / HBM peak) / duration), `append`, `kv_transfer` (request-level KV export /
+max(flops / MFMA peak, bytes / HBM peak) / duration), `roofline.library_gemm_same_box` (what the vendor library's bf16
+GEMM reaches on the same box, for scale), `append`, `kv_transfer` (request-level KV export /
 import, Sec. 3.3.4), `fp8_prefill` (the first chunks' fused launches over a cache of FP8 codes, against the same
 launches over the 16-bit pool), `decode` (one decode iteration of 64 requests x 2048 cached tokens on the same head
 shape, 16-bit and FP8 cache) and `cpu_baseline` (the CPU oracle on this machine's host cores over a bounded sample of the same
@@ -466,6 +467,27 @@ def main():
             "import_frac": round(2 * payload / (imp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         }
         del xbuf
+
+    # ---- for scale: what the vendor library's bf16 GEMM reaches on this machine right now (the 13B layer's QKV projection
+    # on 8192 tokens through torch.matmul, 20 launches back to back between two events); context for roofline.frac, not a target
+    ga = torch.randn((8192, 5120), device=dev).to(torch.bfloat16)
+    gb = torch.randn((5120, 15360), device=dev).to(torch.bfloat16)
+    gc_ = torch.empty((8192, 15360), dtype=torch.bfloat16, device=dev)
+    for _ in range(3):
+        torch.matmul(ga, gb, out=gc_)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(20):
+        torch.matmul(ga, gb, out=gc_)
+    e1.record(stream)
+    e1.synchronize()
+    gemm_ms = e0.elapsed_time(e1) / 20
+    result["roofline"]["library_gemm_same_box"] = {
+        "op": "torch.matmul bf16 8192x5120 @ 5120x15360", "ms": round(gemm_ms, 4),
+        "tflops": round(2 * 8192 * 5120 * 15360 / (gemm_ms * 1e-3) / 1e12, 1),
+        "frac_of_peak": round(2 * 8192 * 5120 * 15360 / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)}
+    del ga, gb, gc_
 
     # ---- the same chunks over a cache of FP8 E4M3 codes (this build's extension): every chunk's fused launch
     # (attention over the codes cached so far + quantising append), repeated on one set of buffers like warm_cache

@@ -93,9 +93,11 @@ typedef struct {
  * stages rather than by row tiles) and tetri_decode_attn keep partial results there: such launches on one
  * handle must not overlap in time; use one handle per stream that runs concurrently.  The attention calls
  * return TETRI_ERR_INVALID_ARG when the handle's previous such launch went to another stream and that stream
- * still has work pending (synchronise the two streams, or use a handle each); the
- * arrival counters they use are zeroed for each launch by the launch before it (and by tetri_create), so
- * no state survives from one launch to the next.
+ * still has work pending (synchronise the two streams, or use a handle each).  No state survives from one
+ * launch to the next: a launch sets the arrival counters it used back to zero, and they are zeroed once more
+ * for each launch by the launch before it (and by tetri_create).  The calls may be captured into a HIP graph
+ * (a stream that is capturing is not asked whether it has work pending); replays of such a graph and launches
+ * outside it may follow each other in any order on one handle, as long as they do not overlap in time.
  * tetri_create checks the configuration (TETRI_ERR_UNSUPPORTED / TETRI_ERR_INVALID_ARG) and
  * that a HIP device is usable (TETRI_ERR_HIP) and stores the handle in *out.
  * A handle must not be used by two threads at once.

@@ -245,6 +245,11 @@ __device__ __forceinline__ int atomic_add_global(int32_t *p, int v)
                                   __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ void store_global(int32_t *p, int32_t v)
+{
+    *reinterpret_cast<__attribute__((address_space(1))) int32_t *>((uintptr_t)p) = v;
+}
+
 // Everything a wavefront needs to know about where its workgroup's keys come from.
 struct KeySource {
     const uint16_t *pages, *k_new, *v_new;

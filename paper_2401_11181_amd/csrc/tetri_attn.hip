@@ -1199,6 +1199,10 @@ __device__ __forceinline__ void tile_job(const AttnParams &kernarg, bool first_j
                 return;
             }
         }
+        // This wavefront is the last of the tile's pieces to arrive: nobody touches the unit's counter any more in this
+        // launch.  It goes back to zero here, so that a launch leaves the counters it used clean whatever runs on
+        // the handle next (the replay of a captured graph uses the counter set it was captured with).
+        if (lane_e == 0) store_global(pe.counters + unit, 0);
         if (J.npieces == 2) {
             finish_pair<D>(pe, grp, J.wf, J.tile_index, J.piece, slot, o, m, ltot, lane_e, row_ok_e, J.seg_cu + t_e, head);
         } else {
@@ -1614,6 +1618,7 @@ __global__ __launch_bounds__(kSlots * KS * 64, 2) void attn_tile_kernel(AttnPara
         if (__builtin_amdgcn_readfirstlane(old_stash[slot]) == ho.npieces - 1) {
             const int head = grp * pd.hpw + (slot & (pd.hpw - 1));
             const int t = ho.t0 + 32 * (slot >> pd.hpw_shift) + (lane & 31);
+            if (lane == 0) store_global(pd.counters + ho.unit, 0);      // (the last to arrive: see tile_job)
             finish_tile<D>(pd, grp, ho.wf, ho.tile_index, ho.npieces, -1, slot, nullptr, 0.f, 0.f, lane, t < ho.n_s, ho.seg_cu + t, head);
         }
     }

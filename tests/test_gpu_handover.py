@@ -142,3 +142,49 @@ def test_overlapping_launches_on_one_handle_are_refused(oracle):
         torch.cuda.synchronize()
         check(out_b, ref_rows, "second stream, after the first has drained")
         assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16))
+
+
+@pytest.mark.parametrize("fp8", [False, True], ids=["16-bit-pool", "fp8-pool"])
+def test_graph_replays_between_eager_launches(oracle, fp8):
+    """A HIP graph that holds an odd number of launches that divide tiles, replayed several times with eager launches of
+    the same kind and synchronisations in between: every replay gives the bits of the eager launch.  (A replay uses the
+    arrival counters it was captured with, whatever the handle has handed out since: every launch leaves the counters
+    it used at zero.)"""
+    if fp8:
+        w = synth.small("graph-fp8", [1024], 256, 8, 8, 128, seed=145)
+        qs, ks, vs, tables = gc.workload_tensors(w)
+        _outs, pool, sess = gc.gpu_prefill_fp8(w, qs, ks, vs, tables, 0.0137, 0.0171)
+        c = sess.n_chunks - 1
+        dq, dk, dv = [t.to(DEV) for t in qs], [t.to(DEV) for t in ks], [t.to(DEV) for t in vs]
+        q, k, v = sess.gather_chunk(dq, c), sess.gather_chunk(dk, c), sess.gather_chunk(dv, c)
+        launch = lambda out: sess.attn_fp8(c, q, k, v, pool, w.scale, 0.0137, 0.0171, 0, out)
+    else:
+        w, sess, c, (q, k, v), pool, _ref_rows = prefilled(oracle, "graph", 144)
+        launch = lambda out: sess.attn(c, q, k, v, pool, w.scale, out)
+    for mode_opts in ({"stream_wgs": 0, "split_min_stages": 2, "split_bias_stages": 0}, {"stream_wgs": 5}, {"stream_wgs": 3}):
+        for key, value in mode_opts.items():
+            sess.handle.tetri_set_option(key, value)
+        eager = torch.zeros_like(q)
+        launch(eager)
+        torch.cuda.synchronize()
+        want = eager.view(torch.int16).clone()
+        outs = [torch.zeros_like(q) for _ in range(3)]
+        tmp = torch.zeros_like(q)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for o in outs:
+                launch(o)
+        for rep in range(4):
+            for o in outs:
+                o.fill_(7.0)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for i, o in enumerate(outs):
+                assert torch.equal(o.view(torch.int16), want), (mode_opts, "replay", rep, "launch", i)
+            for _ in range(rep % 2 + 1):                 # one or two eager launches: the handle's own alternation moves on
+                tmp.fill_(7.0)
+                launch(tmp)
+            torch.cuda.synchronize()
+            assert torch.equal(tmp.view(torch.int16), want), (mode_opts, "eager after replay", rep)

@@ -69,6 +69,17 @@ def test_shapes(oracle, name, variant):
     print(name, run_case(oracle, w, variant=variant))
 
 
+def test_more_than_64_segments_in_a_chunk(oracle, variant):
+    """150 prompts of one to four tokens in chunks of 256: 60 to 130 segments per chunk (the lookup of a tile's segment
+    takes several rounds of 64, stream mode does not apply), tiles of a few rows each, a short last chunk."""
+    rng = np.random.default_rng(150)
+    lens = [int(x) for x in rng.integers(1, 5, size=150)]
+    w = synth.small("many-segments", lens, 256, 4, 2, 128, seed=150)
+    print(run_case(oracle, w, variant=variant))
+    w = synth.small("many-segments-d64", lens[:100], 128, 6, 2, 64, seed=151)
+    print(run_case(oracle, w, variant=variant, fused=True))
+
+
 def test_append_before_attention_gives_same_result(oracle, variant):
     w = synth.small("order", [90, 75, 20], 64, 4, 2, 128, seed=130)
     qs, ks, vs, tables = gc.workload_tensors(w)

@@ -52,6 +52,13 @@ def test_shapes(name, variant):
     print(name, run_case(w, variant))
 
 
+def test_more_than_64_segments_in_a_chunk(variant):
+    rng = np.random.default_rng(152)
+    lens = [int(x) for x in rng.integers(1, 5, size=150)]
+    w = synth.small("fp8-many-segments", lens, 256, 4, 2, 128, seed=152)
+    print(run_case(w, variant))
+
+
 @pytest.mark.parametrize("scales", [(2.0 ** -6, 2.0 ** -5), (0.11, 0.0031), (3.0e-3, 0.4)], ids=["pow2", "coarse-k", "saturating-k"])
 def test_scales_of_the_cache(scales, variant):
     """Coarse scales quantise hard (the oracle reads the same codes: the bar stays), small ones saturate at +-448."""

@@ -41,7 +41,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled
 # by a plain copy of known size.  A profiled figure, not one of this run: (bytes, the summary that holds it).
-PROFILED_TRAFFIC = {("opt13b", "fused"): (76.1e6, "profiles/attn_tile_kernel_opt13b_hbm_traffic.md")}
+PROFILED_TRAFFIC = {("opt13b", "fused"): (76.3e6, "profiles/attn_tile_kernel_opt13b_hbm_traffic.md")}
 
 
 # ---- algorithmic work of a chunk: what the method must do (masked pairs and padding rows count zero)
